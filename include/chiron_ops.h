@@ -1,0 +1,58 @@
+/*
+ * chiron_ops.h: the individual kernels of the decode step, exported so that each can be
+ * checked against the plain definition and timed on its own.  chiron_decode_step (chiron.h)
+ * is the product call; these run exactly the kernels it runs.
+ *
+ * Same conventions as chiron.h: int32 status return, dev/host pointers, `stream` is a
+ * hipStream_t as void*, calls enqueue and do not synchronise.  Activations are fp32,
+ * weights/gains/cache are bf16 bit patterns.
+ */
+#ifndef CHIRON_OPS_H
+#define CHIRON_OPS_H
+
+#include <stdint.h>
+
+#include "chiron.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* out[r][j] = h[r][j] * gain[j] / sqrt(mean_j(h[r][j]^2) + eps); h, out dev fp32 [rows, n]; gain dev bf16 [n]. */
+int32_t chiron_op_rmsnorm(const float *h, const void *gain, int32_t rows, int32_t n, float eps, float *out,
+                          void *stream);
+
+/* A weight matrix repacked into matrix-core tile order (library-owned device copy). */
+typedef struct chiron_linear chiron_linear;
+/* w dev bf16 [N, K] (out, in) row-major; N a multiple of 32... any N >= 1 (padded inside), K a multiple of 16. */
+int32_t chiron_linear_create(const void *w, int32_t N, int32_t K, void *stream, chiron_linear **out);
+int32_t chiron_linear_destroy(chiron_linear *l);
+
+/* y[M,N] = x[M,K] * W^T (accumulate == 0) or y += x * W^T (accumulate != 0, the residual add).
+ * x, y dev fp32 row-major.  x is split into two bf16 terms, products accumulate in fp32. */
+int32_t chiron_op_linear(const chiron_linear *l, const float *x, int32_t M, float *y, int32_t accumulate,
+                         void *stream);
+
+/* SwiGLU fused into the projection's operand load: with gu dev fp32 [M, 2K] holding the gate
+ * values in columns [0,K) and the up values in [K,2K),
+ *     y (+)= (silu(gate) * up) * W^T,   silu(z) = z / (1 + exp(-z)). */
+int32_t chiron_op_swiglu_linear(const chiron_linear *l, const float *gu, int32_t M, float *y, int32_t accumulate,
+                                void *stream);
+
+/* Rotary embedding in place: x dev fp32 [rows, n_heads, d]; row r is rotated for position pos[r]
+ * (pairs (j, j+d/2), angle pos*base^(-2j/d), angles evaluated in fp64). */
+int32_t chiron_op_rope(float *x, int32_t rows, int32_t n_heads, int32_t d, const int32_t *pos, float base,
+                       void *stream);
+
+/* Paged GQA decode attention of one layer: for request i and query head a (KV head a / G)
+ *     out[i][a] = softmax_t(q[i][a] . K_t / sqrt(d)) . V_t   over positions t < ctx_lens[i]
+ * of the request's paged cache.  q, out dev fp32 [batch, n_q_heads*head_dim]; ctx_lens dev
+ * int32 [batch], each >= 1.  Uses the model's attention workspace (split-K partials). */
+int32_t chiron_op_paged_attention(chiron_model *m, const chiron_kvpool *p, int32_t layer, const float *q,
+                                  const int32_t *block_table, const int32_t *ctx_lens, int32_t batch, float *out,
+                                  void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHIRON_OPS_H */

@@ -1,0 +1,468 @@
+// Host side of the C ABI (include/chiron.h, include/chiron_ops.h): handles, argument checks,
+// weight loading, and the sequence of kernel launches that makes one decode step.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <unordered_set>
+#include <vector>
+
+#include "chiron_internal.h"
+
+namespace chiron {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static int32_t dev_alloc(void** p, size_t bytes) {
+    *p = nullptr;
+    hipError_t e = hipMalloc(p, bytes ? bytes : 256);
+    if (e != hipSuccess) {
+        *p = nullptr;
+        (void)hipGetLastError();
+        return fail(CHIRON_ERR_OOM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    }
+    return CHIRON_OK;
+}
+
+static int32_t linear_alloc(Linear& L, int N, int K) {
+    L.N = N;
+    L.K = K;
+    L.Npad = (N + 31) / 32 * 32;
+    L.owned = true;
+    int32_t rc = dev_alloc((void**)&L.w, (size_t)L.Npad * K * 2);
+    if (rc) return rc;
+    if (L.Npad != N) CHIRON_HIP(hipMemset(L.w, 0, (size_t)L.Npad * K * 2));
+    return CHIRON_OK;
+}
+
+static void linear_free(Linear& L) {
+    if (L.owned && L.w) (void)hipFree(L.w);
+    L.w = nullptr;
+}
+
+static int32_t check_config(const chiron_model_config* c) {
+    if (!c) return fail(CHIRON_ERR_INVALID_ARG, "config is null");
+    if (c->dtype != CHIRON_BF16) return fail(CHIRON_ERR_INVALID_ARG, "dtype %d: only CHIRON_BF16 is supported", c->dtype);
+    if (c->n_layers < 1 || c->hidden < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->ffn < 1 || c->vocab < 1 ||
+        c->max_batch < 1 || c->max_blocks_per_seq < 1)
+        return fail(CHIRON_ERR_INVALID_ARG, "config has a non-positive size");
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(CHIRON_ERR_SHAPE, "head_dim %d: must be 64 or 128", c->head_dim);
+    if (c->n_q_heads % c->n_kv_heads != 0) return fail(CHIRON_ERR_SHAPE, "n_q_heads must be a multiple of n_kv_heads");
+    int G = c->n_q_heads / c->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16) return fail(CHIRON_ERR_SHAPE, "query heads per KV head %d: must be 1,2,4,8,16", G);
+    if (c->hidden % 16 != 0 || c->ffn % 16 != 0) return fail(CHIRON_ERR_SHAPE, "hidden and ffn must be multiples of 16");
+    if (c->hidden > 16384) return fail(CHIRON_ERR_SHAPE, "hidden %d: at most 16384", c->hidden);
+    if (!(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f)) return fail(CHIRON_ERR_INVALID_ARG, "rope_base must be > 1 and rms_eps >= 0");
+    return CHIRON_OK;
+}
+
+}  // namespace chiron
+
+using namespace chiron;
+
+extern "C" {
+
+const char* chiron_last_error(void) { return g_err; }
+
+// ---- model ---------------------------------------------------------------------------------------------
+int32_t chiron_model_destroy(chiron_model* m) {
+    if (!m) return CHIRON_OK;
+    for (int l = 0; l < m->cfg.n_layers; ++l) {
+        if (m->qkv) linear_free(m->qkv[l]);
+        if (m->wo) linear_free(m->wo[l]);
+        if (m->gu) linear_free(m->gu[l]);
+        if (m->down) linear_free(m->down[l]);
+    }
+    delete[] m->qkv; delete[] m->wo; delete[] m->gu; delete[] m->down;
+    linear_free(m->lm);
+    void* bufs[] = {m->attn_norm, m->ffn_norm, m->final_norm, m->embed, m->h, m->x, m->qkvb, m->attn, m->gub,
+                    m->cos_t, m->sin_t, m->aws.plan, m->aws.part_o, m->aws.part_ml};
+    for (void* b : bufs)
+        if (b) (void)hipFree(b);
+    delete m;
+    return CHIRON_OK;
+}
+
+int32_t chiron_model_create(const chiron_model_config* cfg, chiron_model** out) {
+    if (!out) return fail(CHIRON_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    int32_t rc = check_config(cfg);
+    if (rc) return rc;
+    chiron_model* m = new (std::nothrow) chiron_model();
+    if (!m) return fail(CHIRON_ERR_OOM, "host allocation failed");
+    m->cfg = *cfg;
+    const int L = cfg->n_layers, H = cfg->hidden, d = cfg->head_dim, F = cfg->ffn;
+    const int qn = cfg->n_q_heads * d, kn = cfg->n_kv_heads * d, B = cfg->max_batch;
+    if (hipGetDevice(&m->device) != hipSuccess) {
+        delete m;
+        return fail(CHIRON_ERR_HIP, "no HIP device is available");
+    }
+    m->qkv = new (std::nothrow) Linear[L]; m->wo = new (std::nothrow) Linear[L];
+    m->gu = new (std::nothrow) Linear[L]; m->down = new (std::nothrow) Linear[L];
+#define TRY(expr)                     \
+    do {                              \
+        rc = (expr);                  \
+        if (rc) {                     \
+            chiron_model_destroy(m);  \
+            return rc;                \
+        }                             \
+    } while (0)
+    if (!m->qkv || !m->wo || !m->gu || !m->down) TRY(fail(CHIRON_ERR_OOM, "host allocation failed"));
+    for (int l = 0; l < L; ++l) {
+        TRY(linear_alloc(m->qkv[l], qn + 2 * kn, H));
+        TRY(linear_alloc(m->wo[l], H, qn));
+        TRY(linear_alloc(m->gu[l], 2 * F, H));
+        TRY(linear_alloc(m->down[l], H, F));
+    }
+    TRY(linear_alloc(m->lm, cfg->vocab, H));
+    TRY(dev_alloc((void**)&m->attn_norm, (size_t)L * H * 2));
+    TRY(dev_alloc((void**)&m->ffn_norm, (size_t)L * H * 2));
+    TRY(dev_alloc((void**)&m->final_norm, (size_t)H * 2));
+    TRY(dev_alloc((void**)&m->embed, (size_t)cfg->vocab * H * 2));
+    TRY(dev_alloc((void**)&m->h, (size_t)B * H * 4));
+    TRY(dev_alloc((void**)&m->x, (size_t)B * H * 4));
+    TRY(dev_alloc((void**)&m->qkvb, (size_t)B * (qn + 2 * kn) * 4));
+    TRY(dev_alloc((void**)&m->attn, (size_t)B * qn * 4));
+    TRY(dev_alloc((void**)&m->gub, (size_t)B * 2 * F * 4));
+    TRY(dev_alloc((void**)&m->cos_t, (size_t)B * (d / 2) * 4));
+    TRY(dev_alloc((void**)&m->sin_t, (size_t)B * (d / 2) * 4));
+    // attention work list: room for a few items per wave slot plus one ragged tail per request
+    m->aws.max_batch = B;
+    m->aws.cap_items = 8192 + 2 * B;
+    TRY(dev_alloc((void**)&m->aws.plan, (size_t)attn_plan_ints(B, m->aws.cap_items) * 4));
+    TRY(dev_alloc((void**)&m->aws.part_o, (size_t)m->aws.cap_items * cfg->n_q_heads * d * 4));
+    TRY(dev_alloc((void**)&m->aws.part_ml, (size_t)m->aws.cap_items * cfg->n_q_heads * 2 * 4));
+#undef TRY
+    *out = m;
+    return CHIRON_OK;
+}
+
+int32_t chiron_model_load_layer(chiron_model* m, int32_t layer, const chiron_layer_weights* w, void* stream) {
+    if (!m || !w) return fail(CHIRON_ERR_INVALID_ARG, "model or weights is null");
+    if (layer < 0 || layer >= m->cfg.n_layers) return fail(CHIRON_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+        return fail(CHIRON_ERR_INVALID_ARG, "a layer weight pointer is null");
+    hipStream_t st = (hipStream_t)stream;
+    const chiron_model_config& c = m->cfg;
+    const int H = c.hidden, d = c.head_dim, F = c.ffn, qn = c.n_q_heads * d, kn = c.n_kv_heads * d;
+    int32_t rc;
+    // fused QKV: rows [q | k | v]; fused gate/up: rows [gate | up]
+    if ((rc = launch_pack_rows((const uint16_t*)w->wq, qn, H, m->qkv[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wk, kn, H, m->qkv[layer].w, qn, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wv, kn, H, m->qkv[layer].w, qn + kn, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wo, H, qn, m->wo[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_gate, F, H, m->gu[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_up, F, H, m->gu[layer].w, F, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_down, H, F, m->down[layer].w, 0, st))) return rc;
+    CHIRON_HIP(hipMemcpyAsync(m->attn_norm + (size_t)layer * H, w->attn_norm, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
+    CHIRON_HIP(hipMemcpyAsync(m->ffn_norm + (size_t)layer * H, w->ffn_norm, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
+    return CHIRON_OK;
+}
+
+int32_t chiron_model_load_head(chiron_model* m, const void* embed, const void* final_norm, const void* lm_head,
+                               void* stream) {
+    if (!m || !embed || !final_norm || !lm_head) return fail(CHIRON_ERR_INVALID_ARG, "model or a weight pointer is null");
+    hipStream_t st = (hipStream_t)stream;
+    const chiron_model_config& c = m->cfg;
+    CHIRON_HIP(hipMemcpyAsync(m->embed, embed, (size_t)c.vocab * c.hidden * 2, hipMemcpyDeviceToDevice, st));
+    CHIRON_HIP(hipMemcpyAsync(m->final_norm, final_norm, (size_t)c.hidden * 2, hipMemcpyDeviceToDevice, st));
+    return launch_pack_rows((const uint16_t*)lm_head, c.vocab, c.hidden, m->lm.w, 0, st);
+}
+
+// ---- KV pool -------------------------------------------------------------------------------------------
+int64_t chiron_kv_block_bytes(const chiron_model* m, int32_t block_size) {
+    if (!m || block_size != kBlockSize) return 0;
+    return (int64_t)m->cfg.n_layers * m->cfg.n_kv_heads * 2 * block_size * m->cfg.head_dim * 2;
+}
+
+int32_t chiron_kv_pool_create(const chiron_model* m, void* dev_mem, uint64_t bytes, int32_t block_size,
+                              chiron_kvpool** out, int32_t* num_blocks_out) {
+    if (!out) return fail(CHIRON_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (!m || !dev_mem) return fail(CHIRON_ERR_INVALID_ARG, "model or dev_mem is null");
+    if (block_size != kBlockSize) return fail(CHIRON_ERR_INVALID_ARG, "block_size %d: must be 16", block_size);
+    if ((uintptr_t)dev_mem & 255) return fail(CHIRON_ERR_INVALID_ARG, "dev_mem must be 256-byte aligned");
+    uint64_t per_block = (uint64_t)chiron_kv_block_bytes(m, block_size);
+    uint64_t nb = bytes / per_block;
+    if (nb < 1) return fail(CHIRON_ERR_OOM, "pool of %llu bytes holds no page (one page is %llu bytes)",
+                            (unsigned long long)bytes, (unsigned long long)per_block);
+    if (nb > 0x7fffffffull / kBlockSize) nb = 0x7fffffffull / kBlockSize;
+    chiron_kvpool* p = new (std::nothrow) chiron_kvpool();
+    if (!p) return fail(CHIRON_ERR_OOM, "host allocation failed");
+    p->block_size = block_size;
+    p->d.base = (uint16_t*)dev_mem;
+    p->d.num_blocks = (int)nb;
+    p->d.n_kv = m->cfg.n_kv_heads;
+    p->d.d = m->cfg.head_dim;
+    p->d.n_layers = m->cfg.n_layers;
+    p->d.layer_stride = (int64_t)nb * m->cfg.n_kv_heads * 2 * kBlockSize * m->cfg.head_dim;
+    *out = p;
+    if (num_blocks_out) *num_blocks_out = (int32_t)nb;
+    return CHIRON_OK;
+}
+
+int32_t chiron_kv_pool_destroy(chiron_kvpool* p) {
+    delete p;
+    return CHIRON_OK;
+}
+
+int32_t chiron_append_kv(chiron_kvpool* p, int32_t layer, const void* k, const void* v, const int32_t* block_table,
+                         int32_t max_blocks_per_seq, const int32_t* seq_idx, const int32_t* pos, int64_t n,
+                         void* stream) {
+    if (!p) return fail(CHIRON_ERR_INVALID_ARG, "pool is null");
+    if (n < 0) return fail(CHIRON_ERR_INVALID_ARG, "n is negative");
+    if (n == 0) return CHIRON_OK;
+    if (layer < 0 || layer >= p->d.n_layers) return fail(CHIRON_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (!k || !v || !block_table || !seq_idx || !pos) return fail(CHIRON_ERR_INVALID_ARG, "a pointer argument is null");
+    if (max_blocks_per_seq < 1) return fail(CHIRON_ERR_INVALID_ARG, "max_blocks_per_seq must be positive");
+    return launch_append_kv(p->d, layer, (const uint16_t*)k, (const uint16_t*)v, block_table, max_blocks_per_seq, seq_idx,
+                            pos, n, (hipStream_t)stream);
+}
+
+int32_t chiron_gather_kv(const chiron_kvpool* p, int32_t layer, const int32_t* block_table_row, int32_t len, void* k_out,
+                         void* v_out, void* stream) {
+    if (!p) return fail(CHIRON_ERR_INVALID_ARG, "pool is null");
+    if (len < 0) return fail(CHIRON_ERR_INVALID_ARG, "len is negative");
+    if (len == 0) return CHIRON_OK;
+    if (layer < 0 || layer >= p->d.n_layers) return fail(CHIRON_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (!block_table_row || !k_out || !v_out) return fail(CHIRON_ERR_INVALID_ARG, "a pointer argument is null");
+    return launch_gather_kv(p->d, layer, block_table_row, len, (uint16_t*)k_out, (uint16_t*)v_out, (hipStream_t)stream);
+}
+
+// ---- the step ------------------------------------------------------------------------------------------
+static int32_t check_step_args(const chiron_model* m, const chiron_kvpool* p, const int32_t* block_table,
+                               const int32_t* seq_lens, const int32_t* tokens, int32_t batch) {
+    if (!m || !p) return fail(CHIRON_ERR_INVALID_ARG, "model or pool is null");
+    if (batch < 0) return fail(CHIRON_ERR_INVALID_ARG, "batch is negative");
+    if (batch > m->cfg.max_batch) return fail(CHIRON_ERR_BATCH_TOO_LARGE, "batch %d exceeds max_batch %d", batch, m->cfg.max_batch);
+    if (batch > 0 && (!block_table || !seq_lens || !tokens)) return fail(CHIRON_ERR_INVALID_ARG, "an index array is null");
+    if (p->d.n_kv != m->cfg.n_kv_heads || p->d.d != m->cfg.head_dim || p->d.n_layers != m->cfg.n_layers)
+        return fail(CHIRON_ERR_INVALID_ARG, "pool was created for a different model shape");
+    return CHIRON_OK;
+}
+
+int32_t chiron_decode_step(chiron_model* m, chiron_kvpool* p, const int32_t* block_table, const int32_t* seq_lens,
+                           const int32_t* tokens, int32_t batch, float* logits, void* stream) {
+    int32_t rc = check_step_args(m, p, block_table, seq_lens, tokens, batch);
+    if (rc) return rc;
+    if (batch == 0) return CHIRON_OK;
+    if (!logits) return fail(CHIRON_ERR_INVALID_ARG, "logits is null");
+    hipStream_t st = (hipStream_t)stream;
+    const chiron_model_config& c = m->cfg;
+    const int H = c.hidden, d = c.head_dim, F = c.ffn, qn = c.n_q_heads * d, kn = c.n_kv_heads * d, B = batch;
+    const int mb = c.max_blocks_per_seq;
+#define STEP(expr) \
+    if ((rc = (expr))) return rc
+    STEP(launch_embed(m->embed, tokens, B, H, m->h, st));
+    STEP(launch_rope_table(seq_lens, B, d, c.rope_base, m->cos_t, m->sin_t, st));
+    STEP(launch_attn_plan(m->aws, seq_lens, 1, B, c.n_kv_heads, st));
+    for (int l = 0; l < c.n_layers; ++l) {
+        STEP(launch_rmsnorm(m->h, m->attn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
+        STEP(launch_linear(m->qkv[l], m->x, H, B, m->qkvb, qn + 2 * kn, 0, PRO_NONE, st));
+        STEP(launch_rope_append(p->d, l, m->qkvb, c.n_q_heads, m->cos_t, m->sin_t, block_table, mb, seq_lens, B, st));
+        STEP(launch_paged_attention(m->aws, p->d, l, m->qkvb, qn + 2 * kn, c.n_q_heads, block_table, mb, seq_lens, 1, B,
+                                    m->attn, qn, st));
+        STEP(launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, st));
+        STEP(launch_rmsnorm(m->h, m->ffn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
+        STEP(launch_linear(m->gu[l], m->x, H, B, m->gub, 2 * F, 0, PRO_NONE, st));
+        STEP(launch_linear(m->down[l], m->gub, 2 * F, B, m->h, H, 1, PRO_SWIGLU, st));
+    }
+    STEP(launch_rmsnorm(m->h, m->final_norm, B, H, c.rms_eps, m->x, st));
+    STEP(launch_linear(m->lm, m->x, H, B, logits, c.vocab, 0, PRO_NONE, st));
+#undef STEP
+    return CHIRON_OK;
+}
+
+int32_t chiron_check_step_inputs_host(const chiron_model_config* cfg, int32_t num_blocks, int32_t block_size,
+                                      const int32_t* block_table, const int32_t* seq_lens, const int32_t* tokens,
+                                      int32_t batch) {
+    if (!cfg) return fail(CHIRON_ERR_INVALID_ARG, "config is null");
+    if (batch < 0) return fail(CHIRON_ERR_INVALID_ARG, "batch is negative");
+    if (batch > cfg->max_batch) return fail(CHIRON_ERR_BATCH_TOO_LARGE, "batch %d exceeds max_batch %d", batch, cfg->max_batch);
+    if (block_size != kBlockSize) return fail(CHIRON_ERR_INVALID_ARG, "block_size %d: must be 16", block_size);
+    if (batch > 0 && (!block_table || !seq_lens || !tokens)) return fail(CHIRON_ERR_INVALID_ARG, "an index array is null");
+    std::unordered_set<int32_t> written;
+    for (int i = 0; i < batch; ++i) {
+        if (tokens[i] < 0 || tokens[i] >= cfg->vocab)
+            return fail(CHIRON_ERR_TOKEN, "tokens[%d] = %d is outside [0, %d)", i, tokens[i], cfg->vocab);
+        if (seq_lens[i] < 0) return fail(CHIRON_ERR_INVALID_ARG, "seq_lens[%d] = %d is negative", i, seq_lens[i]);
+        int64_t need = ((int64_t)seq_lens[i] + 1 + block_size - 1) / block_size;
+        if (need > cfg->max_blocks_per_seq)
+            return fail(CHIRON_ERR_BLOCK_TABLE, "request %d needs %lld pages, block table rows hold %d", i, (long long)need,
+                        cfg->max_blocks_per_seq);
+        const int32_t* row = block_table + (size_t)i * cfg->max_blocks_per_seq;
+        for (int64_t b = 0; b < need; ++b)
+            if (row[b] < 0 || row[b] >= num_blocks)
+                return fail(CHIRON_ERR_BLOCK_TABLE, "block_table[%d][%lld] = %d is not a page of the pool (%d pages)", i,
+                            (long long)b, row[b], num_blocks);
+        int32_t wpage = row[seq_lens[i] / block_size];
+        if (!written.insert(wpage).second)
+            return fail(CHIRON_ERR_BLOCK_TABLE, "page %d is written by more than one request (request %d)", wpage, i);
+    }
+    // a page that one request writes must not be read by another (shared pages are read-only)
+    for (int i = 0; i < batch; ++i) {
+        const int32_t* row = block_table + (size_t)i * cfg->max_blocks_per_seq;
+        int64_t wi = seq_lens[i] / block_size;
+        for (int64_t b = 0; b < wi; ++b)
+            if (written.count(row[b]))
+                return fail(CHIRON_ERR_BLOCK_TABLE, "page %d is read by request %d and written by another", row[b], i);
+    }
+    return CHIRON_OK;
+}
+
+int32_t chiron_validate_step_inputs(const chiron_model* m, const chiron_kvpool* p, const int32_t* block_table,
+                                    const int32_t* seq_lens, const int32_t* tokens, int32_t batch, void* stream) {
+    int32_t rc = check_step_args(m, p, block_table, seq_lens, tokens, batch);
+    if (rc) return rc;
+    if (batch == 0) return CHIRON_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int mb = m->cfg.max_blocks_per_seq;
+    std::vector<int32_t> bt((size_t)batch * mb), sl(batch), tk(batch);
+    CHIRON_HIP(hipMemcpyAsync(bt.data(), block_table, bt.size() * 4, hipMemcpyDeviceToHost, st));
+    CHIRON_HIP(hipMemcpyAsync(sl.data(), seq_lens, sl.size() * 4, hipMemcpyDeviceToHost, st));
+    CHIRON_HIP(hipMemcpyAsync(tk.data(), tokens, tk.size() * 4, hipMemcpyDeviceToHost, st));
+    CHIRON_HIP(hipStreamSynchronize(st));
+    return chiron_check_step_inputs_host(&m->cfg, p->d.num_blocks, p->block_size, bt.data(), sl.data(), tk.data(), batch);
+}
+
+int32_t chiron_step_latency_profile(chiron_model* m, chiron_kvpool* p, const int32_t* block_table,
+                                    const int32_t* seq_lens, const int32_t* tokens, const int32_t* batch_sizes,
+                                    int32_t n_sizes, int32_t warmup, int32_t iters, float* logits_scratch, void* stream,
+                                    chiron_profile_point* out) {
+    if (!batch_sizes || !out) return fail(CHIRON_ERR_INVALID_ARG, "batch_sizes or out is null");
+    if (n_sizes < 0 || warmup < 0 || iters < 1) return fail(CHIRON_ERR_INVALID_ARG, "n_sizes/warmup must be >= 0 and iters >= 1");
+    hipStream_t st = (hipStream_t)stream;
+    for (int k = 0; k < n_sizes; ++k) {
+        int b = batch_sizes[k];
+        if (b < 1) return fail(CHIRON_ERR_INVALID_ARG, "batch_sizes[%d] = %d must be positive", k, b);
+        int32_t rc = check_step_args(m, p, block_table, seq_lens, tokens, b);
+        if (rc) return rc;
+    }
+    std::vector<hipEvent_t> ev((size_t)iters + 1);
+    for (auto& e : ev) CHIRON_HIP(hipEventCreate(&e));
+    int32_t rc = CHIRON_OK;
+    for (int k = 0; k < n_sizes && rc == CHIRON_OK; ++k) {
+        int b = batch_sizes[k];
+        for (int w = 0; w < warmup && rc == CHIRON_OK; ++w)
+            rc = chiron_decode_step(m, p, block_table, seq_lens, tokens, b, logits_scratch, stream);
+        if (rc) break;
+        hipError_t e = hipEventRecord(ev[0], st);
+        for (int it = 0; it < iters && rc == CHIRON_OK && e == hipSuccess; ++it) {
+            rc = chiron_decode_step(m, p, block_table, seq_lens, tokens, b, logits_scratch, stream);
+            e = hipEventRecord(ev[it + 1], st);
+        }
+        if (rc == CHIRON_OK && e == hipSuccess) e = hipStreamSynchronize(st);
+        if (rc == CHIRON_OK && e != hipSuccess) rc = fail(CHIRON_ERR_HIP, "profile: %s", hipGetErrorString(e));
+        if (rc) break;
+        std::vector<double> ms(iters);
+        double sum = 0;
+        for (int it = 0; it < iters; ++it) {
+            float t = 0.f;
+            (void)hipEventElapsedTime(&t, ev[it], ev[it + 1]);
+            ms[it] = t;
+            sum += t;
+        }
+        std::sort(ms.begin(), ms.end());
+        out[k].batch = b;
+        out[k].lat_ms_median = (iters % 2) ? ms[iters / 2] : 0.5 * (ms[iters / 2 - 1] + ms[iters / 2]);
+        int i99 = (int)std::min<double>(iters - 1, std::ceil(0.99 * iters) - 1);
+        out[k].lat_ms_p99 = ms[i99 < 0 ? 0 : i99];
+        out[k].lat_ms_mean = sum / iters;
+        out[k].tokens_per_s = b / (out[k].lat_ms_median * 1e-3);
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    return rc;
+}
+
+// ---- single kernels ------------------------------------------------------------------------------------
+int32_t chiron_op_rmsnorm(const float* h, const void* gain, int32_t rows, int32_t n, float eps, float* out, void* stream) {
+    if (rows < 0 || n < 1) return fail(CHIRON_ERR_INVALID_ARG, "rmsnorm: bad sizes");
+    if (rows == 0) return CHIRON_OK;
+    if (!h || !gain || !out) return fail(CHIRON_ERR_INVALID_ARG, "rmsnorm: a pointer is null");
+    return launch_rmsnorm(h, (const uint16_t*)gain, rows, n, eps, out, (hipStream_t)stream);
+}
+
+int32_t chiron_linear_create(const void* w, int32_t N, int32_t K, void* stream, chiron_linear** out) {
+    if (!out) return fail(CHIRON_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (!w || N < 1 || K < 1) return fail(CHIRON_ERR_INVALID_ARG, "linear: null weight or non-positive size");
+    if (K % 16 != 0) return fail(CHIRON_ERR_SHAPE, "linear: K=%d must be a multiple of 16", K);
+    chiron_linear* l = new (std::nothrow) chiron_linear();
+    if (!l) return fail(CHIRON_ERR_OOM, "host allocation failed");
+    int32_t rc = linear_alloc(l->L, N, K);
+    if (!rc) rc = launch_pack_rows((const uint16_t*)w, N, K, l->L.w, 0, (hipStream_t)stream);
+    if (rc) {
+        linear_free(l->L);
+        delete l;
+        return rc;
+    }
+    *out = l;
+    return CHIRON_OK;
+}
+
+int32_t chiron_linear_destroy(chiron_linear* l) {
+    if (l) {
+        linear_free(l->L);
+        delete l;
+    }
+    return CHIRON_OK;
+}
+
+int32_t chiron_op_linear(const chiron_linear* l, const float* x, int32_t M, float* y, int32_t accumulate, void* stream) {
+    if (!l) return fail(CHIRON_ERR_INVALID_ARG, "linear is null");
+    if (M < 0) return fail(CHIRON_ERR_INVALID_ARG, "M is negative");
+    if (M == 0) return CHIRON_OK;
+    if (!x || !y) return fail(CHIRON_ERR_INVALID_ARG, "linear: a pointer is null");
+    return launch_linear(l->L, x, l->L.K, M, y, l->L.N, accumulate, PRO_NONE, (hipStream_t)stream);
+}
+
+int32_t chiron_op_swiglu_linear(const chiron_linear* l, const float* gu, int32_t M, float* y, int32_t accumulate,
+                                void* stream) {
+    if (!l) return fail(CHIRON_ERR_INVALID_ARG, "linear is null");
+    if (M < 0) return fail(CHIRON_ERR_INVALID_ARG, "M is negative");
+    if (M == 0) return CHIRON_OK;
+    if (!gu || !y) return fail(CHIRON_ERR_INVALID_ARG, "swiglu_linear: a pointer is null");
+    return launch_linear(l->L, gu, 2 * l->L.K, M, y, l->L.N, accumulate, PRO_SWIGLU, (hipStream_t)stream);
+}
+
+int32_t chiron_op_rope(float* x, int32_t rows, int32_t n_heads, int32_t d, const int32_t* pos, float base, void* stream) {
+    if (rows < 0 || n_heads < 1 || d < 2 || (d & 1)) return fail(CHIRON_ERR_INVALID_ARG, "rope: bad sizes");
+    if (rows == 0) return CHIRON_OK;
+    if (!x || !pos) return fail(CHIRON_ERR_INVALID_ARG, "rope: a pointer is null");
+    hipStream_t st = (hipStream_t)stream;
+    float* tab = nullptr;
+    size_t n = (size_t)rows * (d / 2);
+    CHIRON_HIP(hipMallocAsync((void**)&tab, 2 * n * sizeof(float), st));
+    int32_t rc = launch_rope_table(pos, rows, d, base, tab, tab + n, st);
+    if (!rc) rc = launch_rope(x, n_heads * d, n_heads, d, tab, tab + n, rows, st);
+    (void)hipFreeAsync(tab, st);
+    return rc;
+}
+
+int32_t chiron_op_paged_attention(chiron_model* m, const chiron_kvpool* p, int32_t layer, const float* q,
+                                  const int32_t* block_table, const int32_t* ctx_lens, int32_t batch, float* out,
+                                  void* stream) {
+    if (!m || !p) return fail(CHIRON_ERR_INVALID_ARG, "model or pool is null");
+    if (batch < 0) return fail(CHIRON_ERR_INVALID_ARG, "batch is negative");
+    if (batch > m->cfg.max_batch) return fail(CHIRON_ERR_BATCH_TOO_LARGE, "batch %d exceeds max_batch %d", batch, m->cfg.max_batch);
+    if (batch == 0) return CHIRON_OK;
+    if (layer < 0 || layer >= p->d.n_layers) return fail(CHIRON_ERR_INVALID_ARG, "layer %d out of range", layer);
+    if (!q || !block_table || !ctx_lens || !out) return fail(CHIRON_ERR_INVALID_ARG, "attention: a pointer is null");
+    hipStream_t st = (hipStream_t)stream;
+    const int qn = m->cfg.n_q_heads * m->cfg.head_dim;
+    int32_t rc = launch_attn_plan(m->aws, ctx_lens, 0, batch, m->cfg.n_kv_heads, st);
+    if (rc) return rc;
+    return launch_paged_attention(m->aws, p->d, layer, q, qn, m->cfg.n_q_heads, block_table, m->cfg.max_blocks_per_seq,
+                                  ctx_lens, 0, batch, out, qn, st);
+}
+
+}  // extern "C"

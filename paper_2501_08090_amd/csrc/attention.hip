@@ -1,0 +1,344 @@
+// Paged GQA decode attention, split over the context ("split-K") with a wavefront-level online
+// softmax.  gfx950, wave64.
+//
+// One wave owns one work item: (request, KV head, run of consecutive pages).  It streams the
+// K and V tiles of its pages from HBM straight into matrix-core operand registers (the pool's
+// tile orders make each fragment a contiguous 1 KiB read), computes the 16-token x G-head score
+// tile with v_mfma_f32_16x16x32_bf16, keeps the running max / sum per head in registers, and
+// accumulates P*V with v_mfma_f32_16x16x16_bf16 (the score tile's register layout is exactly the
+// operand layout that instruction wants, so P never leaves registers).  q and P enter the matrix
+// cores as two bf16 terms each.  Items write (max, sum, unnormalised output); a second kernel
+// merges the items of a request.
+//
+// The work list is built on the device from seq_lens (the host never sees the lengths), and the
+// attention grid is persistent: each wave strides over the list, which has a fixed length in
+// memory, so every wave terminates.
+#include <cmath>
+#include <cstdlib>
+
+#include "chiron_internal.h"
+#include "device_util.h"
+
+namespace chiron {
+
+// plan buffer layout (int32): [0] n_items, [1] chunk_pages, [2..3] unused,
+// [4, 4+max_batch) first item of request i, [.., +max_batch) number of items of request i,
+// then item_seq[cap_items], item_pg0[cap_items]
+int64_t attn_plan_ints(int max_batch, int cap_items) { return 4 + 2 * (int64_t)max_batch + 2 * (int64_t)cap_items; }
+
+constexpr int kPlanThreads = 1024;
+
+__global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __restrict__ plan, int max_batch, int cap_items,
+                                                                 const int32_t* __restrict__ seq_lens, int len_bias,
+                                                                 int batch, int n_kv, int target_waves, int force_cp) {
+    __shared__ int scan[kPlanThreads];
+    __shared__ int s_cp;
+    int32_t* seq_item0 = plan + 4;
+    int32_t* seq_nch = plan + 4 + max_batch;
+    int32_t* item_seq = plan + 4 + 2 * max_batch;
+    int32_t* item_pg0 = item_seq + cap_items;
+    const int tid = threadIdx.x;
+    const int per = (batch + kPlanThreads - 1) / kPlanThreads;  // requests per thread, contiguous
+    const int i0 = tid * per, i1 = min(batch, i0 + per);
+
+    // total pages
+    int pages = 0;
+    for (int i = i0; i < i1; ++i) pages += (seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize;
+    scan[tid] = pages;
+    __syncthreads();
+    for (int o = kPlanThreads / 2; o > 0; o >>= 1) {
+        if (tid < o) scan[tid] += scan[tid + o];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        int total = scan[0];
+        // pages per item: small enough that the list holds several items per wave slot, large enough that
+        // the per-item partial result stays a small fraction of the bytes the item reads, and such that
+        // the list fits (items <= total/cp + batch).
+        int cp = 16;
+        while (cp > 2 && (int64_t)(total / cp) * n_kv < target_waves) cp >>= 1;
+        while (total / cp + batch > cap_items) cp <<= 1;
+        if (force_cp > 0 && total / force_cp + batch <= cap_items) cp = force_cp;
+        s_cp = cp;
+    }
+    __syncthreads();
+    const int cp = s_cp;
+    __syncthreads();
+
+    // exclusive scan of items per request
+    int items = 0;
+    for (int i = i0; i < i1; ++i) {
+        int np = (seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize;
+        items += (np + cp - 1) / cp;
+    }
+    scan[tid] = items;
+    __syncthreads();
+    for (int o = 1; o < kPlanThreads; o <<= 1) {
+        int v = tid >= o ? scan[tid - o] : 0;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
+    }
+    int off = scan[tid] - items;
+    for (int i = i0; i < i1; ++i) {
+        int np = (seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize;
+        int nch = (np + cp - 1) / cp;
+        seq_item0[i] = off;
+        seq_nch[i] = nch;
+        for (int ch = 0; ch < nch; ++ch) {
+            item_seq[off + ch] = i;
+            item_pg0[off + ch] = ch * cp;
+        }
+        off += nch;
+    }
+    if (tid == kPlanThreads - 1) {
+        plan[0] = scan[tid];
+        plan[1] = cp;
+    }
+}
+
+struct AttnTuning {
+    int grid = kNumCU * 2;
+    int target_waves = 8192;
+    int force_cp = 0;
+};
+static AttnTuning attn_tuning() {
+    static AttnTuning t = [] {
+        AttnTuning x;
+        if (const char* e = getenv("CHIRON_ATTN_GRID")) x.grid = atoi(e);
+        if (const char* e = getenv("CHIRON_ATTN_TARGET_WAVES")) x.target_waves = atoi(e);
+        if (const char* e = getenv("CHIRON_ATTN_CHUNK_PAGES")) x.force_cp = atoi(e);
+        return x;
+    }();
+    return t;
+}
+
+int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv,
+                         hipStream_t st) {
+    AttnTuning t = attn_tuning();
+    attn_plan_kernel<<<1, kPlanThreads, 0, st>>>(ws.plan, ws.max_batch, ws.cap_items, seq_lens, len_bias, batch, n_kv,
+                                                  t.target_waves, t.force_cp);
+    CHIRON_HIP(hipGetLastError());
+    return CHIRON_OK;
+}
+
+// ---- the attention kernel ---------------------------------------------------------------------------
+template <int D, int G>
+__global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, const float* __restrict__ q, int ldq,
+                                                         const int32_t* __restrict__ bt, int max_blocks,
+                                                         const int32_t* __restrict__ seq_lens, int len_bias,
+                                                         const int32_t* __restrict__ plan, int max_batch, int cap_items,
+                                                         float* __restrict__ part_o, float* __restrict__ part_ml,
+                                                         float scale_log2e) {
+    constexpr int KSTEPS = D / 32;  // 16x16x32 MFMAs per score tile; also 16-byte V fragments per page
+    constexpr int NPG = 2;          // pages per pipeline stage
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = gridDim.x * 4;
+    const int n_kv = p.n_kv;
+    const int n_work = plan[0] * n_kv;
+    const int cp = plan[1];
+    const int32_t* item_seq = plan + 4 + 2 * max_batch;
+    const int32_t* item_pg0 = item_seq + cap_items;
+    const int head = lane & 15, lg = lane >> 4;
+    const size_t tile_elems = (size_t)16 * D;
+
+    for (int w = blockIdx.x * 4 + wave; w < n_work; w += n_waves) {
+        const int it = w / n_kv, c = w - it * n_kv;
+        const int i = __builtin_amdgcn_readfirstlane(item_seq[it]);
+        const int pg0 = __builtin_amdgcn_readfirstlane(item_pg0[it]);
+        const int len = __builtin_amdgcn_readfirstlane(seq_lens[i]) + len_bias;
+        const int npages = (len + kBlockSize - 1) / kBlockSize;
+        const int pg1 = min(pg0 + cp, npages);
+        const int32_t* btrow = bt + (size_t)i * max_blocks;
+        const uint16_t* lbase = p.base + (size_t)layer * (size_t)p.layer_stride;
+
+        // q fragments: operand column = head, 8 consecutive dims per lane group; scaled by log2(e)/sqrt(d)
+        uint4 qh[KSTEPS], ql[KSTEPS];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            if (head < G) {
+                const float* qp = q + (size_t)i * ldq + (size_t)(c * G + head) * D + s * 32 + lg * 8;
+                float4 a = *reinterpret_cast<const float4*>(qp), b = *reinterpret_cast<const float4*>(qp + 4);
+                split2(a.x * scale_log2e, a.y * scale_log2e, qh[s].x, ql[s].x);
+                split2(a.z * scale_log2e, a.w * scale_log2e, qh[s].y, ql[s].y);
+                split2(b.x * scale_log2e, b.y * scale_log2e, qh[s].z, ql[s].z);
+                split2(b.z * scale_log2e, b.w * scale_log2e, qh[s].w, ql[s].w);
+            } else {
+                qh[s] = ql[s] = make_uint4(0, 0, 0, 0);
+            }
+        }
+
+        floatx4 o[D / 16];
+#pragma unroll
+        for (int t = 0; t < D / 16; ++t) o[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        float m_run = -INFINITY, l_run = 0.f;
+
+        uint4 kc[NPG][KSTEPS], vc[NPG][KSTEPS], kn[NPG][KSTEPS], vn[NPG][KSTEPS];
+        auto load_group = [&](int pg, uint4 (&kk)[NPG][KSTEPS], uint4 (&vv)[NPG][KSTEPS]) {
+#pragma unroll
+            for (int u = 0; u < NPG; ++u) {
+                int pgx = min(pg + u, pg1 - 1);  // a page past the item's end re-reads the last one (masked below)
+                int blk = __builtin_amdgcn_readfirstlane(btrow[pgx]);
+                const uint16_t* tile = lbase + ((size_t)blk * n_kv + c) * (2 * tile_elems);
+#pragma unroll
+                for (int s = 0; s < KSTEPS; ++s) {
+                    kk[u][s] = *reinterpret_cast<const uint4*>(tile + (size_t)(s * 64 + lane) * 8);
+                    vv[u][s] = *reinterpret_cast<const uint4*>(tile + tile_elems + (size_t)(s * 64 + lane) * 8);
+                }
+            }
+        };
+
+        load_group(pg0, kc, vc);
+        for (int pg = pg0; pg < pg1; pg += NPG) {
+            if (pg + NPG < pg1) load_group(pg + NPG, kn, vn);
+
+            // scores of this stage: s[u][r] = token (pg+u)*16 + 4*lg + r, head = lane%16
+            floatx4 s[NPG];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < NPG; ++u) {
+                s[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int k = 0; k < KSTEPS; ++k) {
+                    bf16x8 a = *reinterpret_cast<bf16x8*>(&kc[u][k]);
+                    s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<bf16x8*>(&qh[k]), s[u], 0, 0, 0);
+                    s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<bf16x8*>(&ql[k]), s[u], 0, 0, 0);
+                }
+                const int len_eff = (pg + u < pg1) ? len : 0;
+                const int tok0 = (pg + u) * 16 + lg * 4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    s[u][r] = (tok0 + r < len_eff) ? s[u][r] : -INFINITY;
+                    mx = fmaxf(mx, s[u][r]);
+                }
+                if ((pg + u + 1) * 16 > len_eff) {
+                    // page holds slots past the end: their V bits may be anything, so clear them
+                    int valid = len_eff - tok0;
+                    uint32_t m01 = (valid > 0 ? 0x0000ffffu : 0u) | (valid > 1 ? 0xffff0000u : 0u);
+                    uint32_t m23 = (valid > 2 ? 0x0000ffffu : 0u) | (valid > 3 ? 0xffff0000u : 0u);
+#pragma unroll
+                    for (int k = 0; k < KSTEPS; ++k) {
+                        vc[u][k].x &= m01; vc[u][k].y &= m23; vc[u][k].z &= m01; vc[u][k].w &= m23;
+                    }
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int t = 0; t < D / 16; ++t) o[t] *= alpha;
+#pragma unroll
+            for (int u = 0; u < NPG; ++u) {
+                float pr[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    pr[r] = __builtin_amdgcn_exp2f(s[u][r] - m_new);
+                    l_run += pr[r];
+                }
+                uint2 ph, pl;
+                split2(pr[0], pr[1], ph.x, pl.x);
+                split2(pr[2], pr[3], ph.y, pl.y);
+                short4v bh = *reinterpret_cast<short4v*>(&ph), bl = *reinterpret_cast<short4v*>(&pl);
+#pragma unroll
+                for (int k = 0; k < KSTEPS; ++k) {
+                    uint2 v0 = make_uint2(vc[u][k].x, vc[u][k].y), v1 = make_uint2(vc[u][k].z, vc[u][k].w);
+                    short4v a0 = *reinterpret_cast<short4v*>(&v0), a1 = *reinterpret_cast<short4v*>(&v1);
+                    o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0, bh, o[2 * k], 0, 0, 0);
+                    o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0, bl, o[2 * k], 0, 0, 0);
+                    o[2 * k + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1, bh, o[2 * k + 1], 0, 0, 0);
+                    o[2 * k + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1, bl, o[2 * k + 1], 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < NPG; ++u)
+#pragma unroll
+                for (int k = 0; k < KSTEPS; ++k) {
+                    kc[u][k] = kn[u][k];
+                    vc[u][k] = vn[u][k];
+                }
+        }
+
+        // each lane group summed its own tokens; combine the four groups
+        l_run += __shfl_xor(l_run, 16);
+        l_run += __shfl_xor(l_run, 32);
+        if (head < G) {
+            const size_t slot = (size_t)w * G + head;
+            if (lg == 0) {
+                part_ml[slot * 2] = m_run;
+                part_ml[slot * 2 + 1] = l_run;
+            }
+#pragma unroll
+            for (int t = 0; t < D / 16; ++t)
+                *reinterpret_cast<float4*>(part_o + slot * D + t * 16 + lg * 4) = make_float4(o[t][0], o[t][1], o[t][2], o[t][3]);
+        }
+    }
+}
+
+// merge the items of one (request, query head): out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j
+template <int D>
+__global__ __launch_bounds__(D) void attn_reduce_kernel(const int32_t* __restrict__ plan, int max_batch, int n_kv, int G,
+                                                        const float* __restrict__ part_o,
+                                                        const float* __restrict__ part_ml, float* __restrict__ out,
+                                                        int ldo) {
+    const int i = blockIdx.x, a = blockIdx.y, c = a / G, j = a % G, d = threadIdx.x;
+    const int item0 = plan[4 + i], nch = plan[4 + max_batch + i];
+    float M = -INFINITY;
+    for (int ch = 0; ch < nch; ++ch) {
+        size_t slot = ((size_t)(item0 + ch) * n_kv + c) * G + j;
+        M = fmaxf(M, part_ml[slot * 2]);
+    }
+    float num = 0.f, den = 0.f;
+    for (int ch = 0; ch < nch; ++ch) {
+        size_t slot = ((size_t)(item0 + ch) * n_kv + c) * G + j;
+        float wgt = __builtin_amdgcn_exp2f(part_ml[slot * 2] - M);
+        den += wgt * part_ml[slot * 2 + 1];
+        num += wgt * part_o[slot * D + d];
+    }
+    out[(size_t)i * ldo + (size_t)a * D + d] = num / den;
+}
+
+template <int D>
+static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p, int layer, const float* q, int ldq,
+                             const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias,
+                             const AttnWorkspace& ws, float scale) {
+#define CHIRON_ATTN(G_)                                                                                              \
+    paged_attn_kernel<D, G_><<<grid, 256, 0, st>>>(p, layer, q, ldq, bt, max_blocks, seq_lens, len_bias, ws.plan,     \
+                                                   ws.max_batch, ws.cap_items, ws.part_o, ws.part_ml, scale)
+    switch (G) {
+        case 1: CHIRON_ATTN(1); break;
+        case 2: CHIRON_ATTN(2); break;
+        case 4: CHIRON_ATTN(4); break;
+        case 8: CHIRON_ATTN(8); break;
+        case 16: CHIRON_ATTN(16); break;
+        default: return fail(CHIRON_ERR_SHAPE, "attention: query heads per KV head must be 1, 2, 4, 8 or 16 (got %d)", G);
+    }
+#undef CHIRON_ATTN
+    return CHIRON_OK;
+}
+
+int32_t launch_paged_attention(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
+                               const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch,
+                               float* out, int ldo, hipStream_t st) {
+    if (batch == 0) return CHIRON_OK;
+    const int G = n_q / p.n_kv;
+    const float scale = (float)(1.4426950408889634 / std::sqrt((double)p.d));
+    AttnTuning t = attn_tuning();
+    dim3 grid(t.grid);
+    int32_t rc;
+    if (p.d == 128) rc = launch_attn_d<128>(G, grid, st, p, layer, q, ldq, bt, max_blocks, seq_lens, len_bias, ws, scale);
+    else if (p.d == 64) rc = launch_attn_d<64>(G, grid, st, p, layer, q, ldq, bt, max_blocks, seq_lens, len_bias, ws, scale);
+    else return fail(CHIRON_ERR_SHAPE, "attention: head_dim must be 64 or 128 (got %d)", p.d);
+    if (rc) return rc;
+    CHIRON_HIP(hipGetLastError());
+    dim3 rgrid(batch, n_q);
+    if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 128, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
+    else attn_reduce_kernel<64><<<rgrid, 64, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
+    CHIRON_HIP(hipGetLastError());
+    return CHIRON_OK;
+}
+
+}  // namespace chiron

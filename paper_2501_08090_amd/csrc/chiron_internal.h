@@ -1,0 +1,106 @@
+// Internal declarations shared by the host API and the kernel launchers.
+// gfx950 only (wave64, MFMA bf16 32x32x16 / 16x16x32 / 16x16x16).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/chiron.h"
+#include "../../include/chiron_ops.h"
+
+namespace chiron {
+
+constexpr int kBlockSize = 16;  // tokens per KV page
+constexpr int kNumCU = 256;
+
+// ---- error plumbing -----------------------------------------------------------------------------
+int32_t fail(int32_t code, const char* fmt, ...);
+#define CHIRON_HIP(expr)                                                                      \
+    do {                                                                                      \
+        hipError_t _e = (expr);                                                               \
+        if (_e != hipSuccess)                                                                 \
+            return ::chiron::fail(CHIRON_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(_e)); \
+    } while (0)
+
+// ---- packed linear layer --------------------------------------------------------------------------
+// Weight W [N,K] (out,in) is stored as 32-row tiles, each tile as K/8 groups of [32 rows][8 k] bf16:
+//   packed[((n/32)*(K/8) + k/8)*256 + (n%32)*8 + k%8] = W[n][k]
+// so one 32x16 MFMA operand fragment (two adjacent k-groups) is 1 KiB of contiguous memory.
+struct Linear {
+    uint16_t* w = nullptr;  // device, packed, N padded to a multiple of 32 with zero rows
+    int N = 0, K = 0, Npad = 0;
+    bool owned = false;
+};
+
+enum Prologue { PRO_NONE = 0, PRO_SWIGLU = 1 };
+
+// y[M,N] (+)= A[M,K] * W^T.  A is fp32 with row stride lda.  PRO_SWIGLU: A[m][k] = silu(src[m][k]) * src[m][K+k].
+// accumulate != 0 adds into y (y holds the residual); otherwise y is overwritten.
+int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
+                      hipStream_t st);
+int32_t launch_pack_rows(const uint16_t* src, int rows, int K, uint16_t* dst_packed, int row_offset, hipStream_t st);
+
+// ---- elementwise / indexing kernels ---------------------------------------------------------------
+int32_t launch_embed(const uint16_t* table, const int32_t* tokens, int batch, int H, float* h, hipStream_t st);
+int32_t launch_rmsnorm(const float* h, const uint16_t* gain, int rows, int n, float eps, float* out, hipStream_t st);
+int32_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
+// cos/sin of pos[i]*base^(-2j/d), j < d/2, evaluated in fp64 and stored as fp32 [rows, d/2] each
+int32_t launch_rope_table(const int32_t* pos, int rows, int d, float base, float* cos_t, float* sin_t, hipStream_t st);
+// rotate x [rows, n_heads, d] (row stride ldx floats) in place with the table
+int32_t launch_rope(float* x, int ldx, int n_heads, int d, const float* cos_t, const float* sin_t, int rows,
+                    hipStream_t st);
+
+struct PoolDesc {
+    uint16_t* base = nullptr;
+    int64_t layer_stride = 0;  // elements
+    int num_blocks = 0, n_kv = 0, d = 0, n_layers = 0;
+};
+// K tile of one (page, kv head): [d/8][16 tok][8];  V tile: [d/32][4 tok-groups][16][2][4 tok]  (see kernels)
+int32_t launch_append_kv(const PoolDesc& p, int layer, const uint16_t* k, const uint16_t* v, const int32_t* bt,
+                         int max_blocks, const int32_t* seq_idx, const int32_t* pos, int64_t n, hipStream_t st);
+int32_t launch_gather_kv(const PoolDesc& p, int layer, const int32_t* bt_row, int len, uint16_t* k_out, uint16_t* v_out,
+                         hipStream_t st);
+// decode-step variant: q,k rotated in fp32 inside the fused qkv row [rows, (nq+2nkv)*d]; k,v rounded to bf16 and
+// written at slot(i, seq_lens[i]); q left rotated in place.
+int32_t launch_rope_append(const PoolDesc& p, int layer, float* qkv, int n_q, const float* cos_t, const float* sin_t,
+                           const int32_t* bt, int max_blocks, const int32_t* seq_lens, int batch, hipStream_t st);
+
+// ---- paged attention ------------------------------------------------------------------------------
+struct AttnWorkspace {
+    int32_t* plan = nullptr;     // [0]=n_items, [1]=chunk_pages; then per-seq and per-item tables (see attention.hip)
+    float* part_o = nullptr;     // [cap_items*n_kv][G][d]
+    float* part_ml = nullptr;    // [cap_items*n_kv][G][2]
+    int cap_items = 0, max_batch = 0;
+};
+int64_t attn_plan_ints(int max_batch, int cap_items);
+// builds the work list for attend lengths len_i = seq_lens[i] + len_bias
+int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv,
+                         hipStream_t st);
+int32_t launch_paged_attention(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
+                               const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch,
+                               float* out, int ldo, hipStream_t st);
+
+}  // namespace chiron
+
+struct chiron_linear {
+    chiron::Linear L;
+};
+
+struct chiron_kvpool {
+    chiron::PoolDesc d;
+    int block_size = 16;
+};
+
+struct chiron_model {
+    chiron_model_config cfg;
+    int device = 0;
+    // packed weights
+    chiron::Linear *qkv = nullptr, *wo = nullptr, *gu = nullptr, *down = nullptr;  // [n_layers]
+    chiron::Linear lm;
+    uint16_t *attn_norm = nullptr, *ffn_norm = nullptr, *final_norm = nullptr;  // [n_layers*H], [H]
+    uint16_t* embed = nullptr;
+    // step workspace, sized for max_batch
+    float *h = nullptr, *x = nullptr, *qkvb = nullptr, *attn = nullptr, *gub = nullptr;
+    float *cos_t = nullptr, *sin_t = nullptr;
+    chiron::AttnWorkspace aws;
+};

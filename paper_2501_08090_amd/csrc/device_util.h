@@ -1,0 +1,48 @@
+// Device-side helpers: bf16 widening/rounding, the two-term bf16 split of fp32 activations,
+// wavefront reductions, LDS-only barrier.  gfx950 (wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace chiron {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// two bf16 packed in a 32-bit word: low half first in memory
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// round-to-nearest-even pair conversion (v_cvt_pk_bf16_f32); first argument lands in the low half
+__device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
+    floatx2 x = {a, b};
+    bf16x2 h = __builtin_convertvector(x, bf16x2);
+    return *reinterpret_cast<uint32_t*>(&h);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float a) { return (uint16_t)(pack_bf16_rne(a, 0.f) & 0xffffu); }
+
+// x ~= hi + lo with hi = bf16(x), lo = bf16(x - hi): 16 significant bits instead of 8, so that
+// rounding the activations costs ~2^-17 relative instead of 2^-9 while the products still run
+// on the bf16 matrix cores (two MFMAs per weight fragment).
+__device__ __forceinline__ void split2(float a, float b, uint32_t& hi, uint32_t& lo) {
+    hi = pack_bf16_rne(a, b);
+    lo = pack_bf16_rne(a - bf16_lo(hi), b - bf16_hi(hi));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Workgroup barrier that waits for this wave's LDS traffic only: global loads already in
+// flight (weight prefetch) stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+}  // namespace chiron

@@ -66,3 +66,37 @@ def as_f64(a):
     if a.dtype == np.uint16:
         return bf16_to_f32(a).astype(np.float64)
     return a.astype(np.float64)
+
+
+# ---- GPU side (only the gpu tests call these) ----------------------------------------------------
+
+def gpu_setup(c, max_batch=None, poison=False, extra_blocks=0):
+    """Build the HIP model and pool for a bf16-storage case and pre-fill the cache through chiron_append_kv."""
+    from paper_2501_08090_amd import binding as B
+    assert c.storage == "bf16"
+    dev = "cuda"
+    model = B.Model(c.m, max_batch or max(c.batch, 1), c.block_table.shape[1])
+    model.load_weights({k: ([a.to(dev) for a in v] if isinstance(v, list) else v.to(dev)) for k, v in c.w_t.items()})
+    nb = c.num_blocks + extra_blocks
+    mem = torch.empty(nb * model.kv_block_bytes(), dtype=torch.uint8, device=dev)
+    if poison:
+        mem.view(torch.int16).fill_(0x7FC0)      # bf16 NaN everywhere: nothing outside live slots may be read
+    else:
+        mem.zero_()
+    pool = B.KVPool(model, memory=mem)
+    assert pool.num_blocks == nb
+    g = Case()
+    g.model, g.pool = model, pool
+    g.block_table = torch.from_numpy(c.block_table).to(dev)
+    g.seq_lens = torch.from_numpy(c.seq_lens).to(dev)
+    g.tokens = torch.from_numpy(c.tokens).to(dev)
+    si, ps = torch.from_numpy(c.seq_idx).to(dev), torch.from_numpy(c.pos).to(dev)
+    for l, (k, v) in enumerate(c.kv_t):
+        pool.append(l, k.to(dev), v.to(dev), g.block_table, si, ps)
+    torch.cuda.synchronize()
+    return g
+
+
+def bits(t):
+    """bf16 GPU tensor -> numpy uint16 bit patterns"""
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)

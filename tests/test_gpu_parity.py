@@ -1,0 +1,272 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Index work (slots, gathers) must be bit-exact; floating point within the
+stated tolerances.  Needs a real MI355X: run with -m gpu."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import chiron_oracle as orc
+from helpers import as_f64, bf16_to_f32, bits, fresh_pool, gpu_setup, make_case
+from paper_2501_08090_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+# bf16 weights/cache are identical on both sides and activations enter the matrix cores as two
+# bf16 terms (relative error 2^-17 per term), so a single kernel differs from the fp32/double
+# oracle by ~1e-5 of the output scale; 1e-4 leaves an order of magnitude.
+KERNEL_TOL = 1e-4
+# whole step: the bar is max|dlogit| <= 2e-2 * std(oracle logits) and argmax agreement >= 99% of rows
+STEP_TOL = 2e-2
+
+
+def B():
+    from paper_2501_08090_amd import binding
+    return binding
+
+
+def rel_err(got, want):
+    return float(np.abs(got - want).max() / (want.std() + 1e-30))
+
+
+# ---- slots: append / gather are pure index work, bit-exact ---------------------------------------
+
+@pytest.mark.parametrize("m,kind,batch", [(I.TINY, "tiny", 4), (dict(I.TINY, head_dim=128, n_kv_heads=2, n_q_heads=8), "tiny", 3)])
+def test_append_gather_bit_exact(m, kind, batch):
+    c = make_case(m=m, batch=batch, kind=kind, seed=11, storage="bf16")
+    g = gpu_setup(c, poison=True)
+    opool = fresh_pool(c)
+    o = 0
+    for i, L in enumerate(c.seq_lens):
+        L = int(L)
+        for l in range(m["n_layers"]):
+            print("gather seq", i, "layer", l, "len", L, flush=True)
+            k, v = g.pool.gather(l, g.block_table[i].contiguous(), L)
+            ok, ov = orc.gather_kv(opool, l, c.block_table[i], L)
+            assert np.array_equal(bits(k), ok) and np.array_equal(bits(v), ov)
+            assert np.array_equal(bits(k), c.kv[l][0][o:o + L])
+        # slots of the sequence's pages that were never written still hold the fill pattern
+        npages = int(I.pages_needed([L])[0])
+        k, v = g.pool.gather(0, g.block_table[i].contiguous(), npages * 16)
+        assert np.all(bits(k)[L:] == 0x7FC0) and np.all(bits(v)[L:] == 0x7FC0)
+        o += L
+
+
+def test_append_overwrites_only_its_slot():
+    c = make_case(batch=3, seed=12, storage="bf16")
+    g = gpu_setup(c)
+    before = [[g.pool.gather(l, g.block_table[i].contiguous(), int(c.seq_lens[i])) for i in range(3)] for l in range(2)]
+    nkv, d = c.m["n_kv_heads"], c.m["head_dim"]
+    newk = I.normal((1, nkv, d), 1.0, 99, "newk").cuda()
+    newv = I.normal((1, nkv, d), 1.0, 99, "newv").cuda()
+    tgt_seq, tgt_pos = 1, int(c.seq_lens[1]) // 2
+    g.pool.append(1, newk, newv, g.block_table, torch.tensor([tgt_seq], dtype=torch.int32, device="cuda"),
+                  torch.tensor([tgt_pos], dtype=torch.int32, device="cuda"))
+    for l in range(2):
+        for i in range(3):
+            k, v = g.pool.gather(l, g.block_table[i].contiguous(), int(c.seq_lens[i]))
+            bk, bv = bits(before[l][i][0]).copy(), bits(before[l][i][1]).copy()
+            if l == 1 and i == tgt_seq:
+                bk[tgt_pos] = bits(newk)[0]
+                bv[tgt_pos] = bits(newv)[0]
+            assert np.array_equal(bits(k), bk) and np.array_equal(bits(v), bv)
+
+
+# ---- single kernels -------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,n", [(1, 256), (5, 4096), (3, 8192), (2, 688)])
+def test_rmsnorm(rows, n):
+    rng = np.random.default_rng(rows * 1000 + n)
+    h = (rng.standard_normal((rows, n)) * 3).astype(np.float32)
+    gain = I.normal((n,), 0.3, 5, "gain", n, mean=1.0)
+    got = B().op_rmsnorm(torch.from_numpy(h).cuda(), gain.cuda(), 1e-5).cpu().numpy()
+    want = np.stack([orc.rmsnorm(h[r], I.to_numpy_storage(gain), 1e-5) for r in range(rows)])
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 256, 256), (4, 512, 256), (4, 1376, 256), (4, 256, 688), (33, 96, 1040),
+                                   (64, 1024, 4096), (100, 160, 512), (130, 4096, 1024), (7, 1000, 64)])
+def test_linear(M, N, K):
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    W = I.normal((N, K), 0.05, 6, "w", N, K)
+    print("linear", M, N, K, flush=True)
+    lin = B().Linear(W.cuda())
+    xg = torch.from_numpy(x).cuda()
+    got = lin(xg).cpu().numpy()
+    want = orc.linear(x, I.to_numpy_storage(W))
+    assert rel_err(got, want) <= KERNEL_TOL
+    # residual form: y += x W^T
+    y0 = rng.standard_normal((M, N)).astype(np.float32)
+    got2 = lin(xg, torch.from_numpy(y0).cuda(), accumulate=True).cpu().numpy()
+    assert rel_err(got2, want + y0) <= KERNEL_TOL
+    lin.close()
+
+
+@pytest.mark.parametrize("M,N,K", [(4, 256, 688), (64, 512, 1408), (40, 96, 64)])
+def test_swiglu_linear(M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    gu = (rng.standard_normal((M, 2 * K)) * 2).astype(np.float32)
+    W = I.normal((N, K), 0.05, 7, "wd", N, K)
+    print("swiglu_linear", M, N, K, flush=True)
+    lin = B().Linear(W.cuda())
+    got = lin.swiglu(torch.from_numpy(gu).cuda()).cpu().numpy()
+    act = orc.swiglu(gu[:, :K], gu[:, K:])
+    want = orc.linear(act, I.to_numpy_storage(W))
+    assert rel_err(got, want) <= KERNEL_TOL
+    lin.close()
+
+
+def test_rope_large_positions():
+    rng = np.random.default_rng(21)
+    pos = np.array([0, 1, 17, 4095, 32767, 131071], np.int32)
+    x = rng.standard_normal((len(pos), 3, 128)).astype(np.float32)
+    got = B().op_rope(torch.from_numpy(x).cuda(), torch.from_numpy(pos).cuda(), 500000.0).cpu().numpy()
+    want = np.stack([orc.rope(x[r], int(pos[r]), 500000.0) for r in range(len(pos))])
+    assert np.abs(got - want).max() <= 2e-6
+    assert np.array_equal(got[0], x[0])
+
+
+@pytest.mark.parametrize("d,nq,nkv,lens", [
+    (64, 4, 2, [1, 15, 16, 17, 128]),
+    (128, 32, 8, [1, 16, 33, 700, 64, 2049]),
+    (128, 8, 1, [5, 300]),
+    (128, 4, 4, [250]),
+])
+def test_paged_attention(d, nq, nkv, lens):
+    m = dict(I.TINY, n_layers=2, head_dim=d, n_q_heads=nq, n_kv_heads=nkv, hidden=256)
+    lens = np.array(lens, np.int32)
+    # the case's seq_lens are the cached tokens; attention here spans exactly those
+    c = make_case(m=m, seed=13, storage="bf16", seq_lens=lens, poison_unused=True)
+    g = gpu_setup(c, poison=True)
+    opool = fresh_pool(c)
+    rng = np.random.default_rng(14)
+    q = (rng.standard_normal((len(lens), nq * d)) * 1.3).astype(np.float32)
+    for layer in (0, 1):
+        print("attention d", d, "nq", nq, "nkv", nkv, "layer", layer, flush=True)
+        got = B().op_paged_attention(g.model, g.pool, layer, torch.from_numpy(q).cuda(), g.block_table, g.seq_lens).cpu().numpy()
+        want = np.stack([orc.paged_attention(opool, layer, c.block_table[i], int(lens[i]), q[i].reshape(nq, d)).reshape(-1)
+                         for i in range(len(lens))])
+        assert np.all(np.isfinite(got))
+        assert np.abs(got - want).max() <= KERNEL_TOL * max(1.0, np.abs(want).max())
+
+
+# ---- the whole step ---------------------------------------------------------------------------------
+
+def run_both(c, g=None, poison=False):
+    g = g or gpu_setup(c, poison=poison)
+    logits = B().decode_step(g.model, g.pool, g.block_table, g.seq_lens, g.tokens)
+    torch.cuda.synchronize()
+    opool = fresh_pool(c)
+    want, slots = orc.decode_step(c.cfg, c.w, opool, c.block_table, c.seq_lens, c.tokens)
+    return g, logits.cpu().numpy(), want, opool
+
+
+def check_logits(got, want, min_agree=0.99):
+    sig = want.std()
+    err = np.abs(got - want).max() / sig
+    agree = float((got.argmax(1) == want.argmax(1)).mean())
+    print("max|d|/sigma = %.3e, argmax agreement = %.4f" % (err, agree), flush=True)
+    assert np.all(np.isfinite(got))
+    assert err <= STEP_TOL
+    assert agree >= min_agree
+    return err
+
+
+@pytest.mark.parametrize("seed,jitter", [(0, 0.0), (1, 0.2)])
+def test_decode_step_tiny_config(seed, jitter):
+    """Tiny decoder (2 layers, hidden 256, 4q/2kv heads of 64, FFN 688, vocab 1024), batch 4, contexts U{16..128},
+    16-token pages, shuffled block table, bf16-rounded copies of the fp32 draws on both sides."""
+    c = make_case(batch=4, seed=seed, storage="bf16", gain_jitter=jitter, poison_unused=True)
+    g, got, want, opool = run_both(c, poison=True)
+    assert got.shape == (4, 1024)
+    err = check_logits(got, want, min_agree=1.0)
+    assert err <= 2e-3   # what the two-term activation split should deliver on two layers
+    B().validate_step_inputs(g.model, g.pool, g.block_table, g.seq_lens, g.tokens)
+    # slot contract: position p of every request now holds the new K/V (value within one bf16 ulp of the
+    # oracle's, since both sides round their own fp32 k,v), every older position is bit-unchanged
+    o = 0
+    for i, L in enumerate(c.seq_lens):
+        L = int(L)
+        for l in range(c.m["n_layers"]):
+            k, v = g.pool.gather(l, g.block_table[i].contiguous(), L + 1)
+            ok, ov = orc.gather_kv(opool, l, c.block_table[i], L + 1)
+            assert np.array_equal(bits(k)[:L], ok[:L]) and np.array_equal(bits(v)[:L], ov[:L])
+            assert np.array_equal(bits(k)[:L], c.kv[l][0][o:o + L])
+            for a, b in ((bits(k)[L], ok[L]), (bits(v)[L], ov[L])):
+                fa, fb = bf16_to_f32(a), bf16_to_f32(b)
+                # one bf16 ulp of the element, plus the fp32-level difference of the two k/v (visible where a
+                # rotated element nearly cancels)
+                assert np.all(np.abs(fa - fb) <= np.abs(fb) * 2.0 ** -7 + 1e-4 * np.abs(fb).max())
+                assert np.mean(a == b) > 0.95
+        o += L
+
+
+def test_decode_step_edge_lengths_and_batch_sizes():
+    # empty context, page boundaries (the new token opens a fresh page at 16 and 32), a longer one
+    c = make_case(seed=3, storage="bf16", seq_lens=[0, 15, 16, 31, 32, 1, 200], poison_unused=True)
+    g, got, want, _ = run_both(c, poison=True)
+    check_logits(got, want, min_agree=1.0)
+    # a request's logits do not depend on the rest of the batch (up to summation order)
+    for b in (1, 3):
+        g2 = gpu_setup(c, poison=True)
+        sub = B().decode_step(g2.model, g2.pool, g2.block_table, g2.seq_lens, g2.tokens, batch=b).cpu().numpy()
+        assert np.abs(sub - want[:b]).max() <= STEP_TOL * want.std()
+    # batch 0 is a no-op
+    B().decode_step(g.model, g.pool, g.block_table, g.seq_lens, g.tokens, batch=0,
+                    logits=torch.empty((1, 1024), device="cuda"))
+
+
+def test_decode_step_batch_permutation_and_layout():
+    c = make_case(batch=6, seed=4, storage="bf16")
+    g, got, want, _ = run_both(c)
+    perm = np.array([4, 2, 0, 5, 1, 3])
+    c2 = make_case(batch=6, seed=4, storage="bf16", shuffle=False, pool_factor=1.0)   # contiguous pages
+    assert np.array_equal(c2.seq_lens, c.seq_lens)
+    g2 = gpu_setup(c2)
+    p = torch.from_numpy(perm).cuda()
+    got2 = B().decode_step(g2.model, g2.pool, g2.block_table[p].contiguous(), g2.seq_lens[p].contiguous(),
+                           g2.tokens[p].contiguous()).cpu().numpy()
+    # permuted batch on a different physical layout: same logits, permuted (fp32 atomics reorder sums)
+    assert np.abs(got2 - got[perm]).max() <= 1e-4 * want.std()
+    check_logits(got2, want[perm], min_agree=1.0)
+
+
+def test_decode_step_medium_shape_d128():
+    """4 layers of the 8B head geometry (32q/8kv heads of 128) at reduced width, batch 70 (two M-tiles, ragged),
+    contexts lognormal: exercises the d=128 attention path, G=4, split contexts and M > 64."""
+    m = dict(I.LLAMA_8B, name="mid", n_layers=4, hidden=1024, ffn=2816, vocab=4096, n_q_heads=32, n_kv_heads=8)
+    lens = I.lognormal_lengths(70, 300, 1, 1500, np.random.default_rng(5))
+    c = make_case(m=m, seed=5, storage="bf16", seq_lens=lens, poison_unused=True)
+    g, got, want, _ = run_both(c, poison=True)
+    check_logits(got, want, min_agree=0.99)
+
+
+def test_repeat_step_is_idempotent_and_profile_runs():
+    c = make_case(batch=4, seed=6, storage="bf16")
+    g, got, want, _ = run_both(c)
+    again = B().decode_step(g.model, g.pool, g.block_table, g.seq_lens, g.tokens).cpu().numpy()
+    assert np.abs(again - got).max() <= 1e-4 * want.std()
+    pts = B().step_latency_profile(g.model, g.pool, g.block_table, g.seq_lens, g.tokens, [1, 2, 4], warmup=1, iters=3)
+    assert [p["batch"] for p in pts] == [1, 2, 4]
+    for p in pts:
+        assert p["lat_ms_median"] > 0 and p["lat_ms_p99"] >= p["lat_ms_median"] and p["tokens_per_s"] > 0
+
+
+def test_error_paths_on_device():
+    c = make_case(batch=4, seed=7, storage="bf16")
+    g = gpu_setup(c)
+    Bd = B()
+    with pytest.raises(Bd.ChironError) as e:
+        Bd.decode_step(g.model, g.pool, g.block_table, g.seq_lens, g.tokens, batch=5,
+                       logits=torch.empty((5, 1024), device="cuda"))
+    assert e.value.code == -3
+    bad = g.block_table.clone(); bad[2, 0] = g.pool.num_blocks + 3
+    with pytest.raises(Bd.ChironError) as e:
+        Bd.validate_step_inputs(g.model, g.pool, bad, g.seq_lens, g.tokens)
+    assert e.value.code == -4
+    badtok = g.tokens.clone(); badtok[1] = 1024
+    with pytest.raises(Bd.ChironError) as e:
+        Bd.validate_step_inputs(g.model, g.pool, g.block_table, g.seq_lens, badtok)
+    assert e.value.code == -7
