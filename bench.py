@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sweep] [--no-cpu-baseline]
+
+A "step" is one chiron_decode_step (every kernel of the path) over one batch of seeded synthetic
+requests whose weights, cache and index arrays are already resident in HBM.  Prints ONE JSON line:
+whole-job decode tokens/s, the roofline position of the dominant kernel (HIP-event timed inside the
+library around each launch), and the CPU oracle timed on the host cores on a bounded sample of the
+same workload.  Everything runs on one GPU; --gpus above 1 is refused.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def kernel_algorithmic(m, batch, ctx_tokens):
+    """per-launch algorithmic HBM bytes and flops of each kernel class (weights + fp32 activations in/out for the
+    projections; 4*n_kv*d bytes per attended token for attention)"""
+    H, d, F, V = m["hidden"], m["head_dim"], m["ffn"], m["vocab"]
+    qn, kn = m["n_q_heads"] * d, m["n_kv_heads"] * d
+    M = batch
+
+    def gemm(N, K, extra_in=0):
+        return dict(bytes=2 * N * K + 4 * M * (K + extra_in) + 4 * M * N, flops=2 * M * N * K)
+
+    return {
+        "qkv": gemm(qn + 2 * kn, H), "o": gemm(H, qn), "gateup": gemm(2 * F, H), "down": gemm(H, F, extra_in=F),
+        "lmhead": gemm(V, H),
+        "attn": dict(bytes=4 * m["n_kv_heads"] * d * ctx_tokens, flops=4 * m["n_q_heads"] * d * ctx_tokens),
+    }
+
+
+def time_steps(B, wl, batch, steps, warmup, logits):
+    import torch
+    for _ in range(warmup):
+        B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, logits=logits, batch=batch)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, logits=logits, batch=batch)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def kernel_times(B, wl, batch, steps, logits):
+    import torch
+    torch.cuda.synchronize()
+    B.kernel_timing_begin(wl.model)
+    for _ in range(steps):
+        B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, logits=logits, batch=batch)
+    return B.kernel_timing_end(wl.model)
+
+
+def cpu_baseline(wl, sample, gpu_logits):
+    """Times the CPU oracle on the requests in `sample` (whole model) and compares its logits with the GPU's."""
+    import numpy as np
+    sys.path.insert(0, os.path.join(ROOT, "oracle"))
+    import chiron_oracle as orc
+    from paper_2501_08090_amd import inputs as I
+    m = wl.m
+    cfg = orc.make_config(m, orc.BF16, orc.BF16)
+    lens = wl.lens[sample]
+    need = I.pages_needed(lens)
+    bt = np.full((len(sample), int(need.max())), -1, np.int32)   # compact pool: placement does not change results
+    o = 0
+    for r, c in enumerate(need):
+        bt[r, :c] = np.arange(o, o + c)
+        o += c
+    pool = orc.Pool(cfg, o, np.uint16)
+    seq_idx, pos = I.prefill_index(lens)
+    for l, (k, v) in enumerate(wl.kv_host):
+        kf = (k.astype(np.uint32) << 16).view(np.float32)
+        vf = (v.astype(np.uint32) << 16).view(np.float32)
+        orc.append_kv(pool, l, kf, vf, bt, seq_idx, pos)
+    t0 = time.perf_counter()
+    logits, _ = orc.decode_step(cfg, wl.w_host, pool, bt, lens, wl.tok[sample])
+    dt = time.perf_counter() - t0
+    sig = float(logits.std())
+    err = float(np.abs(gpu_logits - logits).max() / sig)
+    agree = float((gpu_logits.argmax(1) == logits.argmax(1)).mean())
+    return dict(value=len(sample) / dt, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
+                sample="requests %d..%d of the batch, all %d layers and the LM head, one step (%.1f s)" % (
+                    sample[0], sample[-1], m["n_layers"], dt),
+                seconds=dt), dict(rows=len(sample), max_abs_err_over_sigma=err, argmax_agreement=agree)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b-b64-lognormal800")
+    ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep (prefixes of the batch)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=8)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
+              "Replicas scale by running one instance per GPU." % a.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2501_08090_amd import binding as B
+    from paper_2501_08090_amd import workloads as W
+    B.load()   # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+
+    m0, kind, batch, _ = W.WORKLOADS[a.workload]
+    sample = list(range(min(a.cpu_sample, batch))) if not a.no_cpu_baseline else []
+    t0 = time.time()
+    wl = W.build(a.workload, seed=0, host_seqs=sample, host_weights=bool(sample), log=log)
+    log("workload %s built in %.1f s: batch %d, %d context tokens, pool %d pages" % (
+        a.workload, time.time() - t0, batch, wl.context_tokens, wl.num_blocks))
+    m = wl.m
+    logits = torch.empty((batch, m["vocab"]), dtype=torch.float32, device="cuda")
+
+    sec = time_steps(B, wl, batch, a.steps, a.warmup, logits)
+    gpu_logits = logits[:len(sample)].cpu().numpy() if sample else None
+    tokens_per_s = batch / sec
+    log("step %.3f ms, %.0f tokens/s" % (sec * 1e3, tokens_per_s))
+
+    # per-kernel event timing (separate steps: the events sit between the launches)
+    kt = kernel_times(B, wl, batch, max(2, min(a.steps, 10)), logits)
+    alg = kernel_algorithmic(m, batch, wl.context_tokens)
+    kernels = {}
+    for name, (ms, n) in kt.items():
+        if n == 0:
+            continue
+        avg_us = ms / n * 1e3
+        k = dict(avg_us=round(avg_us, 2), launches_per_step=n // max(2, min(a.steps, 10)))
+        if name in alg:
+            k["GBps"] = round(alg[name]["bytes"] / (avg_us * 1e-6) / 1e9, 1)
+            k["TFLOPs"] = round(alg[name]["flops"] / (avg_us * 1e-6) / 1e12, 2)
+        kernels[name] = k
+    step_kernel_ms = sum(ms for ms, n in kt.values()) / max(2, min(a.steps, 10))
+    dom = max((n for n in kernels if n in alg), key=lambda n: kt[n][0])
+    d_us = kernels[dom]["avg_us"]
+    hbm_frac = alg[dom]["bytes"] / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS
+    mfma_frac = alg[dom]["flops"] / (d_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS
+    if mfma_frac > hbm_frac:
+        roof = dict(bound="mfma", achieved=round(mfma_frac * MFMA_BF16_PEAK_TFLOPS, 2), peak=MFMA_BF16_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=round(mfma_frac, 4), traffic=None)
+    else:
+        roof = dict(bound="hbm", achieved=round(hbm_frac * HBM_PEAK_GBS, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(hbm_frac, 4), traffic=None)
+    roof["kernel"] = {"qkv": "linear_kernel (QKV projection)", "o": "linear_kernel (O projection)",
+                      "gateup": "linear_kernel (gate/up projection)", "down": "linear_kernel (SwiGLU + down projection)",
+                      "lmhead": "linear_kernel (LM head)", "attn": "paged_attn_kernel"}[dom]
+    roof["avg_us"] = d_us
+    roof["algorithmic_bytes_per_launch"] = alg[dom]["bytes"]
+
+    step_bytes = W.algorithmic_bytes(m, wl.lens, batch)
+    out = dict(metric="decode_tokens_per_s", value=round(tokens_per_s, 1), unit="tokens/s", n_gpus=1, steps=a.steps,
+               warmup=a.warmup, ms_per_step=round(sec * 1e3, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="bf16", data="synthetic",
+               config=dict(workload=a.workload, shape=m["name"], batch=batch, context_tokens=wl.context_tokens,
+                           page_tokens=16, pool_pages=wl.num_blocks),
+               roofline=roof,
+               step=dict(algorithmic_GB=round(step_bytes / 1e9, 3), hbm_floor_ms=round(step_bytes / HBM_PEAK_GBS / 1e6, 3),
+                         frac_of_hbm_floor=round(step_bytes / HBM_PEAK_GBS / 1e9 / sec, 4),
+                         sum_of_kernel_ms=round(step_kernel_ms, 3)),
+               kernels=kernels)
+
+    if a.sweep:
+        sizes = [b for b in W.SWEEP_BATCHES if b <= batch]
+        pts = B.step_latency_profile(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, sizes, warmup=2,
+                                     iters=max(3, min(a.steps, 10)), logits=logits)
+        for p in pts:
+            by = W.algorithmic_bytes(m, wl.lens, p["batch"])
+            p["frac_of_hbm_floor"] = round(by / HBM_PEAK_GBS / 1e6 / p["lat_ms_median"], 4)
+            p["context_tokens"] = int(wl.lens[:p["batch"]].astype(np.int64).sum()) + p["batch"]
+            log("batch %4d: %.3f ms  %.0f tok/s  (%.1f%% of HBM floor)" % (
+                p["batch"], p["lat_ms_median"], p["tokens_per_s"], 100 * p["frac_of_hbm_floor"]))
+        out["sweep"] = pts
+
+    if sample:
+        log("timing the CPU oracle on %d requests ..." % len(sample))
+        out["cpu_baseline"], out["parity_sample"] = cpu_baseline(wl, sample, gpu_logits)
+        log("oracle: %.2f tokens/s on %d threads; parity on the sample: max|d|/sigma %.2e, argmax agreement %.3f" % (
+            out["cpu_baseline"]["value"], out["cpu_baseline"]["cores"], out["parity_sample"]["max_abs_err_over_sigma"],
+            out["parity_sample"]["argmax_agreement"]))
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -172,6 +172,22 @@ int32_t chiron_step_latency_profile(chiron_model *m, chiron_kvpool *p, const int
                                     int32_t n_sizes, int32_t warmup, int32_t iters, float *logits_scratch,
                                     void *stream, chiron_profile_point *out);
 
+/* Measurement aid: between _begin and _end every kernel launch of chiron_decode_step on this
+ * model is bracketed by HIP events on the step's stream; _end synchronises `stream` and returns,
+ * per kernel class, the summed event time and the number of launches since _begin.  (The QKV,
+ * O, gate/up, down and LM-head projections are instances of one kernel; a projection whose
+ * partial sums need a cleared output counts that clear in its class.) */
+enum {
+    CHIRON_K_QKV = 0, CHIRON_K_O, CHIRON_K_GATEUP, CHIRON_K_DOWN, CHIRON_K_LMHEAD, CHIRON_K_ATTN, CHIRON_K_ATTN_MERGE,
+    CHIRON_K_RMSNORM, CHIRON_K_ROPE_APPEND, CHIRON_K_OTHER, CHIRON_K_COUNT
+};
+typedef struct {
+    double ms;
+    int64_t launches;
+} chiron_kernel_time;
+int32_t chiron_kernel_timing_begin(chiron_model *m);
+int32_t chiron_kernel_timing_end(chiron_model *m, void *stream, chiron_kernel_time *out /* host [CHIRON_K_COUNT] */);
+
 /* Text of the last failure on this thread ("" if none). */
 const char *chiron_last_error(void);
 

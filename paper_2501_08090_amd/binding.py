@@ -21,7 +21,7 @@ SYMBOLS = [
     "chiron_model_create", "chiron_model_load_layer", "chiron_model_load_head", "chiron_model_destroy",
     "chiron_kv_block_bytes", "chiron_kv_pool_create", "chiron_kv_pool_destroy", "chiron_append_kv", "chiron_gather_kv",
     "chiron_decode_step", "chiron_validate_step_inputs", "chiron_check_step_inputs_host", "chiron_step_latency_profile",
-    "chiron_last_error",
+    "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end",
     "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_op_swiglu_linear",
     "chiron_op_rope", "chiron_op_paged_attention",
 ]
@@ -210,6 +210,24 @@ def step_latency_profile(model, pool, block_table, seq_lens, tokens, batch_sizes
                                               _ptr(logits, torch.float32), _stream(), out))
     return [dict(batch=p.batch, lat_ms_median=p.lat_ms_median, lat_ms_p99=p.lat_ms_p99, lat_ms_mean=p.lat_ms_mean,
                  tokens_per_s=p.tokens_per_s) for p in out]
+
+
+KERNEL_CLASSES = ("qkv", "o", "gateup", "down", "lmhead", "attn", "attn_merge", "rmsnorm", "rope_append", "other")
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("ms", C.c_double), ("launches", C.c_int64)]
+
+
+def kernel_timing_begin(model):
+    _check(load().chiron_kernel_timing_begin(model._h))
+
+
+def kernel_timing_end(model):
+    """-> {class: (total_ms, launches)}"""
+    out = (KernelTime * len(KERNEL_CLASSES))()
+    _check(load().chiron_kernel_timing_end(model._h, _stream(), out))
+    return {n: (out[i].ms, int(out[i].launches)) for i, n in enumerate(KERNEL_CLASSES)}
 
 
 # ---- single kernels -------------------------------------------------------------------------------

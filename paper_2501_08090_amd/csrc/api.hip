@@ -83,6 +83,10 @@ int32_t chiron_model_destroy(chiron_model* m) {
         if (m->down) linear_free(m->down[l]);
     }
     delete[] m->qkv; delete[] m->wo; delete[] m->gu; delete[] m->down;
+    for (auto& t : m->timed) {
+        (void)hipEventDestroy(t.a);
+        (void)hipEventDestroy(t.b);
+    }
     linear_free(m->lm);
     void* bufs[] = {m->attn_norm, m->ffn_norm, m->final_norm, m->embed, m->h, m->x, m->qkvb, m->attn, m->gub,
                     m->cos_t, m->sin_t, m->aws.plan, m->aws.part_o, m->aws.part_ml};
@@ -260,24 +264,39 @@ int32_t chiron_decode_step(chiron_model* m, chiron_kvpool* p, const int32_t* blo
     const chiron_model_config& c = m->cfg;
     const int H = c.hidden, d = c.head_dim, F = c.ffn, qn = c.n_q_heads * d, kn = c.n_kv_heads * d, B = batch;
     const int mb = c.max_blocks_per_seq;
-#define STEP(expr) \
-    if ((rc = (expr))) return rc
-    STEP(launch_embed(m->embed, tokens, B, H, m->h, st));
-    STEP(launch_rope_table(seq_lens, B, d, c.rope_base, m->cos_t, m->sin_t, st));
-    STEP(launch_attn_plan(m->aws, seq_lens, 1, B, c.n_kv_heads, st));
+    // each launch is optionally bracketed by events (chiron_kernel_timing_begin/end)
+#define STEP(cls, expr)                                                          \
+    do {                                                                         \
+        chiron_model::Timed tm{cls, nullptr, nullptr};                           \
+        if (m->timing) {                                                         \
+            CHIRON_HIP(hipEventCreate(&tm.a));                                   \
+            CHIRON_HIP(hipEventCreate(&tm.b));                                   \
+            CHIRON_HIP(hipEventRecord(tm.a, st));                                \
+        }                                                                        \
+        if ((rc = (expr))) return rc;                                            \
+        if (m->timing) {                                                         \
+            CHIRON_HIP(hipEventRecord(tm.b, st));                                \
+            m->timed.push_back(tm);                                              \
+        }                                                                        \
+    } while (0)
+    STEP(CHIRON_K_OTHER, launch_embed(m->embed, tokens, B, H, m->h, st));
+    STEP(CHIRON_K_OTHER, launch_rope_table(seq_lens, B, d, c.rope_base, m->cos_t, m->sin_t, st));
+    STEP(CHIRON_K_OTHER, launch_attn_plan(m->aws, seq_lens, 1, B, c.n_kv_heads, st));
     for (int l = 0; l < c.n_layers; ++l) {
-        STEP(launch_rmsnorm(m->h, m->attn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
-        STEP(launch_linear(m->qkv[l], m->x, H, B, m->qkvb, qn + 2 * kn, 0, PRO_NONE, st));
-        STEP(launch_rope_append(p->d, l, m->qkvb, c.n_q_heads, m->cos_t, m->sin_t, block_table, mb, seq_lens, B, st));
-        STEP(launch_paged_attention(m->aws, p->d, l, m->qkvb, qn + 2 * kn, c.n_q_heads, block_table, mb, seq_lens, 1, B,
-                                    m->attn, qn, st));
-        STEP(launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, st));
-        STEP(launch_rmsnorm(m->h, m->ffn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
-        STEP(launch_linear(m->gu[l], m->x, H, B, m->gub, 2 * F, 0, PRO_NONE, st));
-        STEP(launch_linear(m->down[l], m->gub, 2 * F, B, m->h, H, 1, PRO_SWIGLU, st));
+        STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->attn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
+        STEP(CHIRON_K_QKV, launch_linear(m->qkv[l], m->x, H, B, m->qkvb, qn + 2 * kn, 0, PRO_NONE, st));
+        STEP(CHIRON_K_ROPE_APPEND,
+             launch_rope_append(p->d, l, m->qkvb, c.n_q_heads, m->cos_t, m->sin_t, block_table, mb, seq_lens, B, st));
+        STEP(CHIRON_K_ATTN, launch_attn_main(m->aws, p->d, l, m->qkvb, qn + 2 * kn, c.n_q_heads, block_table, mb, seq_lens,
+                                             1, B, st));
+        STEP(CHIRON_K_ATTN_MERGE, launch_attn_merge(m->aws, p->d, c.n_q_heads, B, m->attn, qn, st));
+        STEP(CHIRON_K_O, launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, st));
+        STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->ffn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
+        STEP(CHIRON_K_GATEUP, launch_linear(m->gu[l], m->x, H, B, m->gub, 2 * F, 0, PRO_NONE, st));
+        STEP(CHIRON_K_DOWN, launch_linear(m->down[l], m->gub, 2 * F, B, m->h, H, 1, PRO_SWIGLU, st));
     }
-    STEP(launch_rmsnorm(m->h, m->final_norm, B, H, c.rms_eps, m->x, st));
-    STEP(launch_linear(m->lm, m->x, H, B, logits, c.vocab, 0, PRO_NONE, st));
+    STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->final_norm, B, H, c.rms_eps, m->x, st));
+    STEP(CHIRON_K_LMHEAD, launch_linear(m->lm, m->x, H, B, logits, c.vocab, 0, PRO_NONE, st));
 #undef STEP
     return CHIRON_OK;
 }
@@ -461,8 +480,42 @@ int32_t chiron_op_paged_attention(chiron_model* m, const chiron_kvpool* p, int32
     const int qn = m->cfg.n_q_heads * m->cfg.head_dim;
     int32_t rc = launch_attn_plan(m->aws, ctx_lens, 0, batch, m->cfg.n_kv_heads, st);
     if (rc) return rc;
-    return launch_paged_attention(m->aws, p->d, layer, q, qn, m->cfg.n_q_heads, block_table, m->cfg.max_blocks_per_seq,
-                                  ctx_lens, 0, batch, out, qn, st);
+    rc = launch_attn_main(m->aws, p->d, layer, q, qn, m->cfg.n_q_heads, block_table, m->cfg.max_blocks_per_seq, ctx_lens,
+                          0, batch, st);
+    if (rc) return rc;
+    return launch_attn_merge(m->aws, p->d, m->cfg.n_q_heads, batch, out, qn, st);
+}
+
+int32_t chiron_kernel_timing_begin(chiron_model* m) {
+    if (!m) return fail(CHIRON_ERR_INVALID_ARG, "model is null");
+    for (auto& t : m->timed) {
+        (void)hipEventDestroy(t.a);
+        (void)hipEventDestroy(t.b);
+    }
+    m->timed.clear();
+    m->timing = true;
+    return CHIRON_OK;
+}
+
+int32_t chiron_kernel_timing_end(chiron_model* m, void* stream, chiron_kernel_time* out) {
+    if (!m || !out) return fail(CHIRON_ERR_INVALID_ARG, "model or out is null");
+    m->timing = false;
+    for (int k = 0; k < CHIRON_K_COUNT; ++k) {
+        out[k].ms = 0.0;
+        out[k].launches = 0;
+    }
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    for (auto& t : m->timed) {
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t.a, t.b);
+        out[t.cls].ms += ms;
+        out[t.cls].launches += 1;
+        (void)hipEventDestroy(t.a);
+        (void)hipEventDestroy(t.b);
+    }
+    m->timed.clear();
+    if (e != hipSuccess) return fail(CHIRON_ERR_HIP, "kernel timing: %s", hipGetErrorString(e));
+    return CHIRON_OK;
 }
 
 }  // extern "C"

@@ -320,9 +320,9 @@ static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p
     return CHIRON_OK;
 }
 
-int32_t launch_paged_attention(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
-                               const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch,
-                               float* out, int ldo, hipStream_t st) {
+int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
+                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch,
+                         hipStream_t st) {
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
     const float scale = (float)(1.4426950408889634 / std::sqrt((double)p.d));
@@ -334,6 +334,13 @@ int32_t launch_paged_attention(const AttnWorkspace& ws, const PoolDesc& p, int l
     else return fail(CHIRON_ERR_SHAPE, "attention: head_dim must be 64 or 128 (got %d)", p.d);
     if (rc) return rc;
     CHIRON_HIP(hipGetLastError());
+    return CHIRON_OK;
+}
+
+int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, int batch, float* out, int ldo,
+                          hipStream_t st) {
+    if (batch == 0) return CHIRON_OK;
+    const int G = n_q / p.n_kv;
     dim3 rgrid(batch, n_q);
     if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 128, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
     else attn_reduce_kernel<64><<<rgrid, 64, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);

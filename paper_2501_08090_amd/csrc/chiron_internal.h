@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/chiron.h"
 #include "../../include/chiron_ops.h"
 
@@ -76,9 +78,11 @@ int64_t attn_plan_ints(int max_batch, int cap_items);
 // builds the work list for attend lengths len_i = seq_lens[i] + len_bias
 int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv,
                          hipStream_t st);
-int32_t launch_paged_attention(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
-                               const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch,
-                               float* out, int ldo, hipStream_t st);
+int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
+                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch,
+                         hipStream_t st);
+int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, int batch, float* out, int ldo,
+                          hipStream_t st);
 
 }  // namespace chiron
 
@@ -103,4 +107,11 @@ struct chiron_model {
     float *h = nullptr, *x = nullptr, *qkvb = nullptr, *attn = nullptr, *gub = nullptr;
     float *cos_t = nullptr, *sin_t = nullptr;
     chiron::AttnWorkspace aws;
+    // optional per-kernel event timing of decode steps
+    struct Timed {
+        int cls;
+        hipEvent_t a, b;
+    };
+    bool timing = false;
+    std::vector<Timed> timed;
 };
