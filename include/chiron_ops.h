@@ -24,7 +24,7 @@ int32_t chiron_op_rmsnorm(const float *h, const void *gain, int32_t rows, int32_
 
 /* A weight matrix repacked into matrix-core tile order (library-owned device copy). */
 typedef struct chiron_linear chiron_linear;
-/* w dev bf16 [N, K] (out, in) row-major; N a multiple of 32... any N >= 1 (padded inside), K a multiple of 16. */
+/* w dev bf16 [N, K] (out, in) row-major; any N >= 1 (padded to 32 inside), K a multiple of 16. */
 int32_t chiron_linear_create(const void *w, int32_t N, int32_t K, void *stream, chiron_linear **out);
 int32_t chiron_linear_destroy(chiron_linear *l);
 
@@ -51,6 +51,12 @@ int32_t chiron_op_rope(float *x, int32_t rows, int32_t n_heads, int32_t d, const
 int32_t chiron_op_paged_attention(chiron_model *m, const chiron_kvpool *p, int32_t layer, const float *q,
                                   const int32_t *block_table, const int32_t *ctx_lens, int32_t batch, float *out,
                                   void *stream);
+
+/* Performance knobs of the kernels, process-wide (0 restores the built-in heuristic where one exists):
+ *   linear_nf (1|2), linear_kstep (4|8), linear_ksplit, linear_target_blocks,
+ *   attn_grid, attn_target_waves, attn_chunk_pages.
+ * They change launch shapes only, never results beyond summation order. Unknown keys are an error. */
+int32_t chiron_set_tuning(const char *key, int32_t value);
 
 #ifdef __cplusplus
 }

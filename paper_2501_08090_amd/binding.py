@@ -23,7 +23,7 @@ SYMBOLS = [
     "chiron_decode_step", "chiron_validate_step_inputs", "chiron_check_step_inputs_host", "chiron_step_latency_profile",
     "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end",
     "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_op_swiglu_linear",
-    "chiron_op_rope", "chiron_op_paged_attention",
+    "chiron_op_rope", "chiron_op_paged_attention", "chiron_set_tuning",
 ]
 
 
@@ -273,6 +273,10 @@ class Linear:
             self.close()
         except Exception:
             pass
+
+
+def set_tuning(key, value):
+    _check(load().chiron_set_tuning(key.encode(), C.c_int32(int(value))))
 
 
 def op_rope(x, pos, base):

@@ -37,10 +37,11 @@ static int32_t linear_alloc(Linear& L, int N, int K) {
     L.N = N;
     L.K = K;
     L.Npad = (N + 31) / 32 * 32;
+    L.Kpad = (K + 127) / 128 * 128;
     L.owned = true;
-    int32_t rc = dev_alloc((void**)&L.w, (size_t)L.Npad * K * 2);
+    int32_t rc = dev_alloc((void**)&L.w, (size_t)L.Npad * L.Kpad * 2);
     if (rc) return rc;
-    if (L.Npad != N) CHIRON_HIP(hipMemset(L.w, 0, (size_t)L.Npad * K * 2));
+    if (L.Npad != N || L.Kpad != K) CHIRON_HIP(hipMemset(L.w, 0, (size_t)L.Npad * L.Kpad * 2));
     return CHIRON_OK;
 }
 
@@ -88,7 +89,7 @@ int32_t chiron_model_destroy(chiron_model* m) {
         (void)hipEventDestroy(t.b);
     }
     linear_free(m->lm);
-    void* bufs[] = {m->attn_norm, m->ffn_norm, m->final_norm, m->embed, m->h, m->x, m->qkvb, m->attn, m->gub,
+    void* bufs[] = {m->attn_norm, m->ffn_norm, m->final_norm, m->embed, m->h, m->x, m->qkvb, m->qb, m->part, m->attn, m->gub,
                     m->cos_t, m->sin_t, m->aws.plan, m->aws.part_o, m->aws.part_ml};
     for (void* b : bufs)
         if (b) (void)hipFree(b);
@@ -135,6 +136,8 @@ int32_t chiron_model_create(const chiron_model_config* cfg, chiron_model** out) 
     TRY(dev_alloc((void**)&m->h, (size_t)B * H * 4));
     TRY(dev_alloc((void**)&m->x, (size_t)B * H * 4));
     TRY(dev_alloc((void**)&m->qkvb, (size_t)B * (qn + 2 * kn) * 4));
+    TRY(dev_alloc((void**)&m->qb, (size_t)B * qn * 4));
+    TRY(dev_alloc((void**)&m->part, (size_t)linear_max_split() * B * std::max(qn + 2 * kn, H) * 4));
     TRY(dev_alloc((void**)&m->attn, (size_t)B * qn * 4));
     TRY(dev_alloc((void**)&m->gub, (size_t)B * 2 * F * 4));
     TRY(dev_alloc((void**)&m->cos_t, (size_t)B * (d / 2) * 4));
@@ -160,13 +163,13 @@ int32_t chiron_model_load_layer(chiron_model* m, int32_t layer, const chiron_lay
     const int H = c.hidden, d = c.head_dim, F = c.ffn, qn = c.n_q_heads * d, kn = c.n_kv_heads * d;
     int32_t rc;
     // fused QKV: rows [q | k | v]; fused gate/up: rows [gate | up]
-    if ((rc = launch_pack_rows((const uint16_t*)w->wq, qn, H, m->qkv[layer].w, 0, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->wk, kn, H, m->qkv[layer].w, qn, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->wv, kn, H, m->qkv[layer].w, qn + kn, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->wo, H, qn, m->wo[layer].w, 0, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->w_gate, F, H, m->gu[layer].w, 0, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->w_up, F, H, m->gu[layer].w, F, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->w_down, H, F, m->down[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wq, qn, H, m->qkv[layer].Kpad, m->qkv[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wk, kn, H, m->qkv[layer].Kpad, m->qkv[layer].w, qn, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wv, kn, H, m->qkv[layer].Kpad, m->qkv[layer].w, qn + kn, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wo, H, qn, m->wo[layer].Kpad, m->wo[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_gate, F, H, m->gu[layer].Kpad, m->gu[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_up, F, H, m->gu[layer].Kpad, m->gu[layer].w, F, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_down, H, F, m->down[layer].Kpad, m->down[layer].w, 0, st))) return rc;
     CHIRON_HIP(hipMemcpyAsync(m->attn_norm + (size_t)layer * H, w->attn_norm, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
     CHIRON_HIP(hipMemcpyAsync(m->ffn_norm + (size_t)layer * H, w->ffn_norm, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
     return CHIRON_OK;
@@ -179,7 +182,7 @@ int32_t chiron_model_load_head(chiron_model* m, const void* embed, const void* f
     const chiron_model_config& c = m->cfg;
     CHIRON_HIP(hipMemcpyAsync(m->embed, embed, (size_t)c.vocab * c.hidden * 2, hipMemcpyDeviceToDevice, st));
     CHIRON_HIP(hipMemcpyAsync(m->final_norm, final_norm, (size_t)c.hidden * 2, hipMemcpyDeviceToDevice, st));
-    return launch_pack_rows((const uint16_t*)lm_head, c.vocab, c.hidden, m->lm.w, 0, st);
+    return launch_pack_rows((const uint16_t*)lm_head, c.vocab, c.hidden, m->lm.Kpad, m->lm.w, 0, st);
 }
 
 // ---- KV pool -------------------------------------------------------------------------------------------
@@ -279,24 +282,29 @@ int32_t chiron_decode_step(chiron_model* m, chiron_kvpool* p, const int32_t* blo
             m->timed.push_back(tm);                                              \
         }                                                                        \
     } while (0)
+    const int msplit = linear_max_split();
+    int ks_res = 0, ks_qkv = 1;  // K-slices waiting in m->part for the residual stream / of the QKV projection
     STEP(CHIRON_K_OTHER, launch_embed(m->embed, tokens, B, H, m->h, st));
     STEP(CHIRON_K_OTHER, launch_rope_table(seq_lens, B, d, c.rope_base, m->cos_t, m->sin_t, st));
     STEP(CHIRON_K_OTHER, launch_attn_plan(m->aws, seq_lens, 1, B, c.n_kv_heads, st));
     for (int l = 0; l < c.n_layers; ++l) {
-        STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->attn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
-        STEP(CHIRON_K_QKV, launch_linear(m->qkv[l], m->x, H, B, m->qkvb, qn + 2 * kn, 0, PRO_NONE, st));
+        // h += (slices of the previous down projection); x = norm(h)
+        STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->attn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
+        STEP(CHIRON_K_QKV, launch_linear(m->qkv[l], m->x, H, B, m->qkvb, qn + 2 * kn, 0, PRO_NONE, m->part, msplit, &ks_qkv, st));
         STEP(CHIRON_K_ROPE_APPEND,
-             launch_rope_append(p->d, l, m->qkvb, c.n_q_heads, m->cos_t, m->sin_t, block_table, mb, seq_lens, B, st));
-        STEP(CHIRON_K_ATTN, launch_attn_main(m->aws, p->d, l, m->qkvb, qn + 2 * kn, c.n_q_heads, block_table, mb, seq_lens,
-                                             1, B, st));
+             launch_rope_append(p->d, l, ks_qkv > 1 ? m->part : m->qkvb, ks_qkv, c.n_q_heads, m->cos_t, m->sin_t, block_table,
+                                mb, seq_lens, B, m->qb, st));
+        STEP(CHIRON_K_ATTN, launch_attn_main(m->aws, p->d, l, m->qb, qn, c.n_q_heads, block_table, mb, seq_lens, 1, B, st));
         STEP(CHIRON_K_ATTN_MERGE, launch_attn_merge(m->aws, p->d, c.n_q_heads, B, m->attn, qn, st));
-        STEP(CHIRON_K_O, launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, st));
-        STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->ffn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
-        STEP(CHIRON_K_GATEUP, launch_linear(m->gu[l], m->x, H, B, m->gub, 2 * F, 0, PRO_NONE, st));
-        STEP(CHIRON_K_DOWN, launch_linear(m->down[l], m->gub, 2 * F, B, m->h, H, 1, PRO_SWIGLU, st));
+        STEP(CHIRON_K_O, launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, m->part, msplit, &ks_res, st));
+        if (ks_res == 1) ks_res = 0;  // written straight into h
+        STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->ffn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
+        STEP(CHIRON_K_GATEUP, launch_linear(m->gu[l], m->x, H, B, m->gub, 2 * F, 0, PRO_NONE, nullptr, 1, nullptr, st));
+        STEP(CHIRON_K_DOWN, launch_linear(m->down[l], m->gub, 2 * F, B, m->h, H, 1, PRO_SWIGLU, m->part, msplit, &ks_res, st));
+        if (ks_res == 1) ks_res = 0;
     }
-    STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->final_norm, B, H, c.rms_eps, m->x, st));
-    STEP(CHIRON_K_LMHEAD, launch_linear(m->lm, m->x, H, B, logits, c.vocab, 0, PRO_NONE, st));
+    STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->final_norm, B, H, c.rms_eps, m->x, st));
+    STEP(CHIRON_K_LMHEAD, launch_linear(m->lm, m->x, H, B, logits, c.vocab, 0, PRO_NONE, nullptr, 1, nullptr, st));
 #undef STEP
     return CHIRON_OK;
 }
@@ -407,7 +415,7 @@ int32_t chiron_op_rmsnorm(const float* h, const void* gain, int32_t rows, int32_
     if (rows < 0 || n < 1) return fail(CHIRON_ERR_INVALID_ARG, "rmsnorm: bad sizes");
     if (rows == 0) return CHIRON_OK;
     if (!h || !gain || !out) return fail(CHIRON_ERR_INVALID_ARG, "rmsnorm: a pointer is null");
-    return launch_rmsnorm(h, (const uint16_t*)gain, rows, n, eps, out, (hipStream_t)stream);
+    return launch_rmsnorm(const_cast<float*>(h), nullptr, 0, (const uint16_t*)gain, rows, n, eps, out, (hipStream_t)stream);
 }
 
 int32_t chiron_linear_create(const void* w, int32_t N, int32_t K, void* stream, chiron_linear** out) {
@@ -418,7 +426,7 @@ int32_t chiron_linear_create(const void* w, int32_t N, int32_t K, void* stream, 
     chiron_linear* l = new (std::nothrow) chiron_linear();
     if (!l) return fail(CHIRON_ERR_OOM, "host allocation failed");
     int32_t rc = linear_alloc(l->L, N, K);
-    if (!rc) rc = launch_pack_rows((const uint16_t*)w, N, K, l->L.w, 0, (hipStream_t)stream);
+    if (!rc) rc = launch_pack_rows((const uint16_t*)w, N, K, l->L.Kpad, l->L.w, 0, (hipStream_t)stream);
     if (rc) {
         linear_free(l->L);
         delete l;
@@ -436,12 +444,26 @@ int32_t chiron_linear_destroy(chiron_linear* l) {
     return CHIRON_OK;
 }
 
+// the projection as the decode step launches it (K sliced into a workspace when the grid would otherwise be
+// too small), followed by the plain sum of the slices that the step's consumers do on the fly
+static int32_t op_linear_common(const Linear& L, const float* x, int lda, int M, float* y, int accumulate, int prologue,
+                                hipStream_t st) {
+    float* part = nullptr;
+    const int msplit = linear_max_split();
+    CHIRON_HIP(hipMallocAsync((void**)&part, (size_t)msplit * M * L.N * sizeof(float), st));
+    int ks = 1;
+    int32_t rc = launch_linear(L, x, lda, M, y, L.N, accumulate, prologue, part, msplit, &ks, st);
+    if (!rc && ks > 1) rc = launch_reduce_partials(part, ks, (int64_t)M * L.N, y, accumulate, st);
+    (void)hipFreeAsync(part, st);
+    return rc;
+}
+
 int32_t chiron_op_linear(const chiron_linear* l, const float* x, int32_t M, float* y, int32_t accumulate, void* stream) {
     if (!l) return fail(CHIRON_ERR_INVALID_ARG, "linear is null");
     if (M < 0) return fail(CHIRON_ERR_INVALID_ARG, "M is negative");
     if (M == 0) return CHIRON_OK;
     if (!x || !y) return fail(CHIRON_ERR_INVALID_ARG, "linear: a pointer is null");
-    return launch_linear(l->L, x, l->L.K, M, y, l->L.N, accumulate, PRO_NONE, (hipStream_t)stream);
+    return op_linear_common(l->L, x, l->L.K, M, y, accumulate, PRO_NONE, (hipStream_t)stream);
 }
 
 int32_t chiron_op_swiglu_linear(const chiron_linear* l, const float* gu, int32_t M, float* y, int32_t accumulate,
@@ -450,7 +472,7 @@ int32_t chiron_op_swiglu_linear(const chiron_linear* l, const float* gu, int32_t
     if (M < 0) return fail(CHIRON_ERR_INVALID_ARG, "M is negative");
     if (M == 0) return CHIRON_OK;
     if (!gu || !y) return fail(CHIRON_ERR_INVALID_ARG, "swiglu_linear: a pointer is null");
-    return launch_linear(l->L, gu, 2 * l->L.K, M, y, l->L.N, accumulate, PRO_SWIGLU, (hipStream_t)stream);
+    return op_linear_common(l->L, gu, 2 * l->L.K, M, y, accumulate, PRO_SWIGLU, (hipStream_t)stream);
 }
 
 int32_t chiron_op_rope(float* x, int32_t rows, int32_t n_heads, int32_t d, const int32_t* pos, float base, void* stream) {
@@ -484,6 +506,21 @@ int32_t chiron_op_paged_attention(chiron_model* m, const chiron_kvpool* p, int32
                           0, batch, st);
     if (rc) return rc;
     return launch_attn_merge(m->aws, p->d, m->cfg.n_q_heads, batch, out, qn, st);
+}
+
+int32_t chiron_set_tuning(const char* key, int32_t value) {
+    if (!key) return fail(CHIRON_ERR_INVALID_ARG, "key is null");
+    Tuning& t = tuning();
+    struct { const char* k; int* p; } tab[] = {
+        {"linear_nf", &t.linear_nf}, {"linear_kstep", &t.linear_kstep}, {"linear_ksplit", &t.linear_ksplit},
+        {"linear_target_blocks", &t.linear_target_blocks}, {"attn_grid", &t.attn_grid},
+        {"attn_target_waves", &t.attn_target_waves}, {"attn_chunk_pages", &t.attn_chunk_pages}};
+    for (auto& e : tab)
+        if (!strcmp(e.k, key)) {
+            *e.p = value;
+            return CHIRON_OK;
+        }
+    return fail(CHIRON_ERR_INVALID_ARG, "unknown tuning key '%s'", key);
 }
 
 int32_t chiron_kernel_timing_begin(chiron_model* m) {

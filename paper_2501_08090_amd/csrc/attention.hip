@@ -97,27 +97,11 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     }
 }
 
-struct AttnTuning {
-    int grid = kNumCU * 2;
-    int target_waves = 8192;
-    int force_cp = 0;
-};
-static AttnTuning attn_tuning() {
-    static AttnTuning t = [] {
-        AttnTuning x;
-        if (const char* e = getenv("CHIRON_ATTN_GRID")) x.grid = atoi(e);
-        if (const char* e = getenv("CHIRON_ATTN_TARGET_WAVES")) x.target_waves = atoi(e);
-        if (const char* e = getenv("CHIRON_ATTN_CHUNK_PAGES")) x.force_cp = atoi(e);
-        return x;
-    }();
-    return t;
-}
-
 int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv,
                          hipStream_t st) {
-    AttnTuning t = attn_tuning();
+    const Tuning& t = tuning();
     attn_plan_kernel<<<1, kPlanThreads, 0, st>>>(ws.plan, ws.max_batch, ws.cap_items, seq_lens, len_bias, batch, n_kv,
-                                                  t.target_waves, t.force_cp);
+                                                  t.attn_target_waves, t.attn_chunk_pages);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -278,27 +262,46 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
     }
 }
 
-// merge the items of one (request, query head): out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j
+// merge the items of one (request, query head): out = sum_j 2^(m_j - M) o_j / sum_j 2^(m_j - M) l_j.
+// 256 threads = 8 item slices x 32 lanes of float4 (D = 128) or 16 slices x 16 lanes (D = 64); slice k takes
+// items k, k+S, ...; the slices are combined through LDS in a fixed order.
 template <int D>
-__global__ __launch_bounds__(D) void attn_reduce_kernel(const int32_t* __restrict__ plan, int max_batch, int n_kv, int G,
-                                                        const float* __restrict__ part_o,
-                                                        const float* __restrict__ part_ml, float* __restrict__ out,
-                                                        int ldo) {
-    const int i = blockIdx.x, a = blockIdx.y, c = a / G, j = a % G, d = threadIdx.x;
+__global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restrict__ plan, int max_batch, int n_kv, int G,
+                                                          const float* __restrict__ part_o,
+                                                          const float* __restrict__ part_ml, float* __restrict__ out,
+                                                          int ldo) {
+    constexpr int LANES = D / 4, S = 256 / LANES;
+    __shared__ float4 s_num[S][LANES];
+    __shared__ float s_den[S];
+    const int i = blockIdx.x, a = blockIdx.y, c = a / G, j = a % G;
+    const int sl = threadIdx.x / LANES, ln = threadIdx.x % LANES;
     const int item0 = plan[4 + i], nch = plan[4 + max_batch + i];
     float M = -INFINITY;
-    for (int ch = 0; ch < nch; ++ch) {
-        size_t slot = ((size_t)(item0 + ch) * n_kv + c) * G + j;
-        M = fmaxf(M, part_ml[slot * 2]);
-    }
-    float num = 0.f, den = 0.f;
-    for (int ch = 0; ch < nch; ++ch) {
+    for (int ch = 0; ch < nch; ++ch) M = fmaxf(M, part_ml[(((size_t)(item0 + ch) * n_kv + c) * G + j) * 2]);
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    float den = 0.f;
+    for (int ch = sl; ch < nch; ch += S) {
         size_t slot = ((size_t)(item0 + ch) * n_kv + c) * G + j;
         float wgt = __builtin_amdgcn_exp2f(part_ml[slot * 2] - M);
         den += wgt * part_ml[slot * 2 + 1];
-        num += wgt * part_o[slot * D + d];
+        float4 o = *reinterpret_cast<const float4*>(part_o + slot * D + ln * 4);
+        num.x += wgt * o.x; num.y += wgt * o.y; num.z += wgt * o.z; num.w += wgt * o.w;
     }
-    out[(size_t)i * ldo + (size_t)a * D + d] = num / den;
+    s_num[sl][ln] = num;
+    if (ln == 0) s_den[sl] = den;
+    __syncthreads();
+    if (sl == 0) {
+        float dsum = 0.f;
+        float4 n4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < S; ++k) {
+            dsum += s_den[k];
+            float4 t = s_num[k][ln];
+            n4.x += t.x; n4.y += t.y; n4.z += t.z; n4.w += t.w;
+        }
+        float inv = 1.0f / dsum;
+        *reinterpret_cast<float4*>(out + (size_t)i * ldo + (size_t)a * D + ln * 4) =
+            make_float4(n4.x * inv, n4.y * inv, n4.z * inv, n4.w * inv);
+    }
 }
 
 template <int D>
@@ -326,8 +329,8 @@ int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, 
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
     const float scale = (float)(1.4426950408889634 / std::sqrt((double)p.d));
-    AttnTuning t = attn_tuning();
-    dim3 grid(t.grid);
+    const Tuning& t = tuning();
+    dim3 grid(t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);
     int32_t rc;
     if (p.d == 128) rc = launch_attn_d<128>(G, grid, st, p, layer, q, ldq, bt, max_blocks, seq_lens, len_bias, ws, scale);
     else if (p.d == 64) rc = launch_attn_d<64>(G, grid, st, p, layer, q, ldq, bt, max_blocks, seq_lens, len_bias, ws, scale);
@@ -342,8 +345,8 @@ int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, i
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
     dim3 rgrid(batch, n_q);
-    if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 128, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
-    else attn_reduce_kernel<64><<<rgrid, 64, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
+    if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
+    else attn_reduce_kernel<64><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }

@@ -26,25 +26,46 @@ int32_t fail(int32_t code, const char* fmt, ...);
 
 // ---- packed linear layer --------------------------------------------------------------------------
 // Weight W [N,K] (out,in) is stored as 32-row tiles, each tile as K/8 groups of [32 rows][8 k] bf16:
-//   packed[((n/32)*(K/8) + k/8)*256 + (n%32)*8 + k%8] = W[n][k]
-// so one 32x16 MFMA operand fragment (two adjacent k-groups) is 1 KiB of contiguous memory.
+//   packed[((n/32)*(Kpad/8) + k/8)*256 + (n%32)*8 + k%8] = W[n][k]
+// so one 32x16 MFMA operand fragment (two adjacent k-groups) is 1 KiB of contiguous memory.  N is padded to a
+// multiple of 32 and K to a multiple of 128 with zeros, so the kernel's loads need no bounds checks.
 struct Linear {
-    uint16_t* w = nullptr;  // device, packed, N padded to a multiple of 32 with zero rows
-    int N = 0, K = 0, Npad = 0;
+    uint16_t* w = nullptr;  // device, packed and zero-padded
+    int N = 0, K = 0, Npad = 0, Kpad = 0;
     bool owned = false;
 };
 
 enum Prologue { PRO_NONE = 0, PRO_SWIGLU = 1 };
 
-// y[M,N] (+)= A[M,K] * W^T.  A is fp32 with row stride lda.  PRO_SWIGLU: A[m][k] = silu(src[m][k]) * src[m][K+k].
-// accumulate != 0 adds into y (y holds the residual); otherwise y is overwritten.
+// Performance knobs (0 = built-in heuristic); see chiron_set_tuning.
+struct Tuning {
+    int linear_nf = 0;              // 32-column tiles per wave (1 or 2)
+    int linear_kstep = 4;           // 16-wide k-steps per LDS chunk (4 or 8)
+    int linear_ksplit = 0;          // forced number of K-slices
+    int linear_target_blocks = 256; // K is sliced until the grid has about this many workgroups
+    int attn_grid = 0;              // workgroups of the persistent attention grid
+    int attn_target_waves = 8192;   // work items aimed for when choosing pages per item
+    int attn_chunk_pages = 0;       // forced pages per item
+};
+Tuning& tuning();
+
+// C[M,N] = A[M,K] * W^T.  A is fp32 with row stride lda.  PRO_SWIGLU: A[m][k] = silu(src[m][k]) * src[m][K+k].
+// If the launch slices K (only when `part` is given; at most max_split slices), slice s stores its partial product
+// at part[s][M][N] and *ksplit_out = number of slices: the caller's consumer adds them up.  Otherwise the result
+// goes to y (y += if accumulate) and *ksplit_out = 1.
 int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
-                      hipStream_t st);
-int32_t launch_pack_rows(const uint16_t* src, int rows, int K, uint16_t* dst_packed, int row_offset, hipStream_t st);
+                      float* part, int max_split, int* ksplit_out, hipStream_t st);
+int linear_max_split();
+int32_t launch_reduce_partials(const float* part, int ks, int64_t n, float* y, int accumulate, hipStream_t st);
+int32_t launch_pack_rows(const uint16_t* src, int rows, int K, int Kpad, uint16_t* dst_packed, int row_offset,
+                         hipStream_t st);
 
 // ---- elementwise / indexing kernels ---------------------------------------------------------------
 int32_t launch_embed(const uint16_t* table, const int32_t* tokens, int batch, int H, float* h, hipStream_t st);
-int32_t launch_rmsnorm(const float* h, const uint16_t* gain, int rows, int n, float eps, float* out, hipStream_t st);
+// out = rmsnorm(h) * gain.  With ks > 0 the row first absorbs the K-slices of the projection that feeds the
+// residual stream: h += sum_s part[s] (h is rewritten), then the norm is taken.
+int32_t launch_rmsnorm(float* h, const float* part, int ks, const uint16_t* gain, int rows, int n, float eps, float* out,
+                       hipStream_t st);
 int32_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 // cos/sin of pos[i]*base^(-2j/d), j < d/2, evaluated in fp64 and stored as fp32 [rows, d/2] each
 int32_t launch_rope_table(const int32_t* pos, int rows, int d, float base, float* cos_t, float* sin_t, hipStream_t st);
@@ -62,10 +83,12 @@ int32_t launch_append_kv(const PoolDesc& p, int layer, const uint16_t* k, const 
                          int max_blocks, const int32_t* seq_idx, const int32_t* pos, int64_t n, hipStream_t st);
 int32_t launch_gather_kv(const PoolDesc& p, int layer, const int32_t* bt_row, int len, uint16_t* k_out, uint16_t* v_out,
                          hipStream_t st);
-// decode-step variant: q,k rotated in fp32 inside the fused qkv row [rows, (nq+2nkv)*d]; k,v rounded to bf16 and
-// written at slot(i, seq_lens[i]); q left rotated in place.
-int32_t launch_rope_append(const PoolDesc& p, int layer, float* qkv, int n_q, const float* cos_t, const float* sin_t,
-                           const int32_t* bt, int max_blocks, const int32_t* seq_lens, int batch, hipStream_t st);
+// decode-step variant: the fused qkv row [rows, (nq+2nkv)*d] is the sum of ks slices qkv[s] (slice stride
+// rows*ld); q and k are rotated in fp32; q goes to q_out [rows, nq*d]; k, v are rounded to bf16 and written at
+// slot(i, seq_lens[i]).
+int32_t launch_rope_append(const PoolDesc& p, int layer, const float* qkv, int ks, int n_q, const float* cos_t,
+                           const float* sin_t, const int32_t* bt, int max_blocks, const int32_t* seq_lens, int batch,
+                           float* q_out, hipStream_t st);
 
 // ---- paged attention ------------------------------------------------------------------------------
 struct AttnWorkspace {
@@ -104,7 +127,8 @@ struct chiron_model {
     uint16_t *attn_norm = nullptr, *ffn_norm = nullptr, *final_norm = nullptr;  // [n_layers*H], [H]
     uint16_t* embed = nullptr;
     // step workspace, sized for max_batch
-    float *h = nullptr, *x = nullptr, *qkvb = nullptr, *attn = nullptr, *gub = nullptr;
+    float *h = nullptr, *x = nullptr, *qkvb = nullptr, *qb = nullptr, *attn = nullptr, *gub = nullptr;
+    float* part = nullptr;  // K-slice workspace of the projections: [max_split][max_batch][max(qkv width, hidden)]
     float *cos_t = nullptr, *sin_t = nullptr;
     chiron::AttnWorkspace aws;
     // optional per-kernel event timing of decode steps

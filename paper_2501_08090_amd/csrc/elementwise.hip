@@ -30,30 +30,53 @@ int32_t launch_embed(const uint16_t* table, const int32_t* tokens, int batch, in
 }
 
 // ---- RMSNorm: one workgroup per row, row held in registers, wavefront + LDS reduction -------------------
-template <int VPT>  // float4 vectors per thread; covers n <= 256*4*VPT
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ h, const uint16_t* __restrict__ gain,
-                                                      int n, float eps, float* __restrict__ out) {
-    __shared__ float red[4];
-    const float* row = h + (size_t)blockIdx.x * n;
+// Also the place where a K-sliced projection into the residual stream is summed: h += sum_s part[s].  The
+// slice loads of a thread are independent, so they are issued four at a time.
+template <int THREADS, int VPT>  // float4 vectors per thread; covers n <= THREADS*4*VPT
+__global__ __launch_bounds__(THREADS) void rmsnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int ks,
+                                                          size_t part_stride, const uint16_t* __restrict__ gain, int n,
+                                                          float eps, float* __restrict__ out) {
+    __shared__ float red[THREADS / 64];
+    float* row = h + (size_t)blockIdx.x * n;
+    const float* prow = part + (size_t)blockIdx.x * n;
     float* orow = out + (size_t)blockIdx.x * n;
     float4 v[VPT];
     float ss = 0.f;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
-        int j = (i * 256 + threadIdx.x) * 4;
+        int j = (i * THREADS + threadIdx.x) * 4;
         if (j < n) {
             v[i] = *reinterpret_cast<const float4*>(row + j);
+            if (ks > 0) {
+                int s = 0;
+                for (; s + 4 <= ks; s += 4) {
+                    float4 t[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) t[u] = *reinterpret_cast<const float4*>(prow + (size_t)(s + u) * part_stride + j);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        v[i].x += t[u].x; v[i].y += t[u].y; v[i].z += t[u].z; v[i].w += t[u].w;
+                    }
+                }
+                for (; s < ks; ++s) {
+                    float4 t = *reinterpret_cast<const float4*>(prow + (size_t)s * part_stride + j);
+                    v[i].x += t.x; v[i].y += t.y; v[i].z += t.z; v[i].w += t.w;
+                }
+                *reinterpret_cast<float4*>(row + j) = v[i];
+            }
             ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
         }
     }
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    float tot = red[0] + red[1] + red[2] + red[3];
+    float tot = 0.f;
+#pragma unroll
+    for (int k = 0; k < THREADS / 64; ++k) tot += red[k];
     float inv = 1.0f / sqrtf(tot / (float)n + eps);
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
-        int j = (i * 256 + threadIdx.x) * 4;
+        int j = (i * THREADS + threadIdx.x) * 4;
         if (j < n) {
             uint2 g = *reinterpret_cast<const uint2*>(gain + j);
             float4 o;
@@ -66,13 +89,15 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     }
 }
 
-int32_t launch_rmsnorm(const float* h, const uint16_t* gain, int rows, int n, float eps, float* out, hipStream_t st) {
+int32_t launch_rmsnorm(float* h, const float* part, int ks, const uint16_t* gain, int rows, int n, float eps, float* out,
+                       hipStream_t st) {
     if (rows == 0) return CHIRON_OK;
-    if (n % 4 != 0 || n > 256 * 4 * 16) return fail(CHIRON_ERR_SHAPE, "rmsnorm: n=%d must be a multiple of 4, <= 16384", n);
-    if (n <= 1024) rmsnorm_kernel<1><<<rows, 256, 0, st>>>(h, gain, n, eps, out);
-    else if (n <= 4096) rmsnorm_kernel<4><<<rows, 256, 0, st>>>(h, gain, n, eps, out);
-    else if (n <= 8192) rmsnorm_kernel<8><<<rows, 256, 0, st>>>(h, gain, n, eps, out);
-    else rmsnorm_kernel<16><<<rows, 256, 0, st>>>(h, gain, n, eps, out);
+    if (n % 4 != 0 || n > 16384) return fail(CHIRON_ERR_SHAPE, "rmsnorm: n=%d must be a multiple of 4, <= 16384", n);
+    size_t ps = (size_t)rows * n;
+    if (n <= 1024) rmsnorm_kernel<256, 1><<<rows, 256, 0, st>>>(h, part, ks, ps, gain, n, eps, out);
+    else if (n <= 4096) rmsnorm_kernel<1024, 1><<<rows, 1024, 0, st>>>(h, part, ks, ps, gain, n, eps, out);
+    else if (n <= 8192) rmsnorm_kernel<1024, 2><<<rows, 1024, 0, st>>>(h, part, ks, ps, gain, n, eps, out);
+    else rmsnorm_kernel<1024, 4><<<rows, 1024, 0, st>>>(h, part, ks, ps, gain, n, eps, out);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -204,48 +229,62 @@ int32_t launch_gather_kv(const PoolDesc& p, int layer, const int32_t* bt_row, in
     return CHIRON_OK;
 }
 
-// ---- decode step: rotate q and k, round k and v to bf16, write them at slot(i, seq_lens[i]) ----------------
-__global__ __launch_bounds__(256) void rope_append_kernel(PoolDesc p, int layer, float* __restrict__ qkv, int n_q,
-                                                          const float* __restrict__ cos_t,
-                                                          const float* __restrict__ sin_t,
-                                                          const int32_t* __restrict__ bt, int max_blocks,
-                                                          const int32_t* __restrict__ seq_lens) {
-    int i = blockIdx.x, d = p.d, half = d / 2;
-    int ld = (n_q + 2 * p.n_kv) * d;
-    float* row = qkv + (size_t)i * ld;
-    int ps = seq_lens[i];
-    int block = bt[(size_t)i * max_blocks + ps / kBlockSize];
-    int t = ps % kBlockSize;
-    const float* ct = cos_t + (size_t)i * half;
-    const float* sn = sin_t + (size_t)i * half;
-    // q heads then k heads: rotate pairs (j, j+half)
-    for (int e = threadIdx.x; e < (n_q + p.n_kv) * half; e += 256) {
-        int hd = e / half, j = e % half;
-        float c = ct[j], s = sn[j];
-        float a = row[hd * d + j], b = row[hd * d + j + half];
-        float ra = a * c - b * s, rb = b * c + a * s;
-        if (hd < n_q) {
-            row[hd * d + j] = ra;
-            row[hd * d + j + half] = rb;
-        } else {
-            int kvh = hd - n_q;
-            size_t tb = tile_base(p, layer, block, kvh);
-            p.base[tb + k_off(t, j)] = f32_to_bf16_rne(ra);
-            p.base[tb + k_off(t, j + half)] = f32_to_bf16_rne(rb);
+// ---- decode step: sum the K-slices of the QKV projection, rotate q and k, round k and v to bf16, write them
+// at slot(i, seq_lens[i]).  One wave per (request, head): lane j owns dims j, j+64, ... of the head. ------------
+__global__ __launch_bounds__(64) void rope_append_kernel(PoolDesc p, int layer, const float* __restrict__ qkv, int ks,
+                                                         size_t slice_stride, int n_q,
+                                                         const float* __restrict__ cos_t,
+                                                         const float* __restrict__ sin_t,
+                                                         const int32_t* __restrict__ bt, int max_blocks,
+                                                         const int32_t* __restrict__ seq_lens,
+                                                         float* __restrict__ q_out) {
+    const int i = blockIdx.x, hd = blockIdx.y, d = p.d, half = d / 2;
+    const int ld = (n_q + 2 * p.n_kv) * d;
+    const float* row = qkv + (size_t)i * ld + (size_t)hd * d;
+    // sum over the K-slices, four independent loads in flight at a time, slices added in ascending order
+    auto val = [&](int e) {
+        const float* q = row + e;
+        float v = 0.f;
+        int s = 0;
+        for (; s + 4 <= ks; s += 4) {
+            float t0 = q[(size_t)s * slice_stride], t1 = q[(size_t)(s + 1) * slice_stride];
+            float t2 = q[(size_t)(s + 2) * slice_stride], t3 = q[(size_t)(s + 3) * slice_stride];
+            v += t0; v += t1; v += t2; v += t3;
         }
-    }
-    const float* vrow = row + (n_q + p.n_kv) * d;
-    for (int e = threadIdx.x; e < p.n_kv * d; e += 256) {
-        int kvh = e / d, dd = e % d;
-        size_t tb = tile_base(p, layer, block, kvh);
-        p.base[tb + 16 * d + v_off(t, dd)] = f32_to_bf16_rne(vrow[e]);
+        for (; s < ks; ++s) v += q[(size_t)s * slice_stride];
+        return v;
+    };
+    const int ps = seq_lens[i];
+    const int block = bt[(size_t)i * max_blocks + ps / kBlockSize];
+    const int t = ps % kBlockSize;
+    if (hd < n_q + p.n_kv) {
+        for (int j = threadIdx.x; j < half; j += 64) {
+            float c = cos_t[(size_t)i * half + j], s = sin_t[(size_t)i * half + j];
+            float a = val(j), b = val(j + half);
+            float ra = a * c - b * s, rb = b * c + a * s;
+            if (hd < n_q) {
+                float* qrow = q_out + (size_t)i * n_q * d + (size_t)hd * d;
+                qrow[j] = ra;
+                qrow[j + half] = rb;
+            } else {
+                size_t tb = tile_base(p, layer, block, hd - n_q);
+                p.base[tb + k_off(t, j)] = f32_to_bf16_rne(ra);
+                p.base[tb + k_off(t, j + half)] = f32_to_bf16_rne(rb);
+            }
+        }
+    } else {
+        size_t tb = tile_base(p, layer, block, hd - n_q - p.n_kv);
+        for (int e = threadIdx.x; e < d; e += 64) p.base[tb + 16 * d + v_off(t, e)] = f32_to_bf16_rne(val(e));
     }
 }
 
-int32_t launch_rope_append(const PoolDesc& p, int layer, float* qkv, int n_q, const float* cos_t, const float* sin_t,
-                           const int32_t* bt, int max_blocks, const int32_t* seq_lens, int batch, hipStream_t st) {
+int32_t launch_rope_append(const PoolDesc& p, int layer, const float* qkv, int ks, int n_q, const float* cos_t,
+                           const float* sin_t, const int32_t* bt, int max_blocks, const int32_t* seq_lens, int batch,
+                           float* q_out, hipStream_t st) {
     if (batch == 0) return CHIRON_OK;
-    rope_append_kernel<<<batch, 256, 0, st>>>(p, layer, qkv, n_q, cos_t, sin_t, bt, max_blocks, seq_lens);
+    size_t stride = (size_t)batch * (n_q + 2 * p.n_kv) * p.d;
+    dim3 grid(batch, n_q + 2 * p.n_kv);
+    rope_append_kernel<<<grid, 64, 0, st>>>(p, layer, qkv, ks, stride, n_q, cos_t, sin_t, bt, max_blocks, seq_lens, q_out);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }

@@ -5,7 +5,9 @@
 // Work split: a workgroup of 4 waves owns 4*NF tiles of 32 output columns (one wave = NF tiles),
 // one M-tile of 32*MT rows and one slice of K.  Weights are read exactly once per M-tile; the
 // activation chunk of the current K-slice is shared by the 4 waves through LDS.  With more than
-// one K-slice the partial sums are combined with fp32 atomics in the output.
+// one K-slice each slice stores its partial product in a workspace [slice][M][N]; the kernel that
+// consumes the projection (residual add + RMSNorm, or RoPE) sums the slices while it reads them,
+// in a fixed order, so results are reproducible run to run.
 #include <cstdlib>
 
 #include "chiron_internal.h"
@@ -14,47 +16,53 @@
 namespace chiron {
 
 // ---- weight repacking -------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void pack_rows_kernel(const uint16_t* __restrict__ src, int rows, int K,
+__global__ __launch_bounds__(256) void pack_rows_kernel(const uint16_t* __restrict__ src, int rows, int K, int Kpad,
                                                         uint16_t* __restrict__ dst, int row_offset) {
-    int kgroups = K / 8;
+    int kgroups = K / 8, pgroups = Kpad / 8;
     int64_t total = (int64_t)rows * kgroups;
     for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
         int r = (int)(t / kgroups), kg = (int)(t % kgroups);
         int n = r + row_offset;
         uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)r * K + (size_t)kg * 8);
-        *reinterpret_cast<uint4*>(dst + ((size_t)(n / 32) * kgroups + kg) * 256 + (size_t)(n % 32) * 8) = v;
+        *reinterpret_cast<uint4*>(dst + ((size_t)(n / 32) * pgroups + kg) * 256 + (size_t)(n % 32) * 8) = v;
     }
 }
 
-int32_t launch_pack_rows(const uint16_t* src, int rows, int K, uint16_t* dst_packed, int row_offset, hipStream_t st) {
+int32_t launch_pack_rows(const uint16_t* src, int rows, int K, int Kpad, uint16_t* dst_packed, int row_offset,
+                         hipStream_t st) {
     if (rows == 0) return CHIRON_OK;
     int64_t total = (int64_t)rows * (K / 8);
     int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
-    pack_rows_kernel<<<blocks, 256, 0, st>>>(src, rows, K, dst_packed, row_offset);
+    pack_rows_kernel<<<blocks, 256, 0, st>>>(src, rows, K, Kpad, dst_packed, row_offset);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
 
 // ---- the kernel ------------------------------------------------------------------------------------------
+// Pipeline per workgroup: weights sit in a ring of KS*NF register fragments per wave; as soon as the MFMAs of
+// k-step s have been issued, slot s is reloaded with the same k-step of the NEXT chunk, so about one chunk of
+// weight loads (KS*NF KiB per wave) is always in flight.  Activations are double-buffered in LDS: while chunk c
+// is consumed, chunk c+1 is written to the other buffer and chunk c+2 is on its way from L2 into registers;
+// one barrier per chunk.
 template <int MT, int NF, int KS, int PRO>
-__global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict__ Wp, int Npad, int Nreal, int K,
+__global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict__ Wp, int Npad, int Nreal, int K, int Kpad,
                                                      const float* __restrict__ A, int lda, int M,
                                                      float* __restrict__ Y, int ldy, int chunks_per_split,
-                                                     int use_atomic) {
+                                                     int mode, size_t part_stride) {
     constexpr int MROWS = 32 * MT;
     constexpr int RS = MROWS + 1;      // LDS row stride in 16-byte units (+1 breaks the power-of-two stride)
     constexpr int KG = 2 * KS;         // 8-wide k-groups per chunk
     constexpr int KC = 16 * KS;        // k per chunk
     constexpr int TASKS = MROWS * KG;  // 8-float staging tasks per chunk
-    constexpr int TPT = (TASKS + 255) / 256;
+    static_assert(TASKS % 256 == 0, "staging assumes whole passes of the workgroup");
+    constexpr int TPT = TASKS / 256;
 
-    __shared__ uint4 lds_hi[KG * RS];
-    __shared__ uint4 lds_lo[KG * RS];
+    __shared__ uint4 lds_hi[2][KG * RS];
+    __shared__ uint4 lds_lo[2][KG * RS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m0 = blockIdx.z * MROWS;
     const int tile0 = (blockIdx.x * 4 + wave) * NF;  // first 32-column tile of this wave
-    const int kgroups = K / 8;
     const int chunks_total = (K + KC - 1) / KC;
     const int c_begin = blockIdx.y * chunks_per_split;
     int c_end = c_begin + chunks_per_split;
@@ -68,26 +76,24 @@ __global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict_
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[f][t][r] = 0.f;
 
-    uint4 wnext[KS][NF];
+    uint4 w[KS][NF];
     float4 areg[TPT][2];
     float4 ureg[PRO == PRO_SWIGLU ? TPT : 1][2];
 
-    auto load_w = [&](int c) {
-        int kbase = c * KC;
+    // The loop body holds no divergent branch: every load is unconditional on a clamped address (the packed
+    // weights are zero-padded in K to a whole chunk, out-of-range activation rows/columns are zeroed by a
+    // select), so the compiler can count outstanding loads exactly and never drains the queue.
+    const int kgroups = Kpad / 8;
+    const uint16_t* wp[NF];
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            int kk = kbase + s * 16;
+    for (int f = 0; f < NF; ++f) {
+        int tile = min(tile0 + f, Npad / 32 - 1);  // a wave past the last tile recomputes it; its stores are masked
+        wp[f] = Wp + ((size_t)tile * kgroups + (lane >> 5)) * 256 + (lane & 31) * 8;
+    }
+    auto load_w = [&](int c, int s) {
+        size_t off = (size_t)(c * KC + s * 16) * 32;
 #pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                int tile = tile0 + f;
-                if (kk < K && tile * 32 < Npad) {
-                    const uint16_t* p = Wp + ((size_t)tile * kgroups + (kk >> 3) + (lane >> 5)) * 256 + (lane & 31) * 8;
-                    wnext[s][f] = *reinterpret_cast<const uint4*>(p);
-                } else {
-                    wnext[s][f] = make_uint4(0, 0, 0, 0);
-                }
-            }
-        }
+        for (int f = 0; f < NF; ++f) w[s][f] = *reinterpret_cast<const uint4*>(wp[f] + off);
     };
     auto load_a = [&](int c) {
         int kbase = c * KC;
@@ -96,27 +102,22 @@ __global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict_
             int task = tid + i * 256;
             int kg = task % KG, m = task / KG;
             int k = kbase + kg * 8;
-            bool ok = (TASKS % 256 == 0 || task < TASKS) && (m0 + m < M) && (k < K);
-            if (ok) {
-                const float* p = A + (size_t)(m0 + m) * lda + k;
-                areg[i][0] = *reinterpret_cast<const float4*>(p);
-                areg[i][1] = *reinterpret_cast<const float4*>(p + 4);
-                if (PRO == PRO_SWIGLU) {
-                    ureg[i][0] = *reinterpret_cast<const float4*>(p + K);
-                    ureg[i][1] = *reinterpret_cast<const float4*>(p + K + 4);
-                }
-            } else {
-                areg[i][0] = areg[i][1] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (PRO == PRO_SWIGLU) ureg[i][0] = ureg[i][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+            const float* p = A + (size_t)min(m0 + m, M - 1) * lda + min(k, K - 8);
+            areg[i][0] = *reinterpret_cast<const float4*>(p);
+            areg[i][1] = *reinterpret_cast<const float4*>(p + 4);
+            if (PRO == PRO_SWIGLU) {
+                ureg[i][0] = *reinterpret_cast<const float4*>(p + K);
+                ureg[i][1] = *reinterpret_cast<const float4*>(p + K + 4);
             }
         }
     };
-    auto stage_a = [&]() {
+    auto stage_a = [&](int c, int buf) {
+        int kbase = c * KC;
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
             int task = tid + i * 256;
-            if (TASKS % 256 != 0 && task >= TASKS) continue;
             int kg = task % KG, m = task / KG;
+            const bool ok = (m0 + m < M) && (kbase + kg * 8 < K);
             float v[8] = {areg[i][0].x, areg[i][0].y, areg[i][0].z, areg[i][0].w,
                           areg[i][1].x, areg[i][1].y, areg[i][1].z, areg[i][1].w};
             if (PRO == PRO_SWIGLU) {
@@ -125,53 +126,67 @@ __global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict_
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = v[e] / (1.0f + __expf(-v[e])) * u[e];
             }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = ok ? v[e] : 0.f;
             uint4 hi, lo;
             split2(v[0], v[1], hi.x, lo.x);
             split2(v[2], v[3], hi.y, lo.y);
             split2(v[4], v[5], hi.z, lo.z);
             split2(v[6], v[7], hi.w, lo.w);
-            lds_hi[kg * RS + m] = hi;
-            lds_lo[kg * RS + m] = lo;
+            lds_hi[buf][kg * RS + m] = hi;
+            lds_lo[buf][kg * RS + m] = lo;
         }
     };
+    auto mma_step = [&](int buf, int s) {
+        bf16x8 ah[MT], al[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            int idx = (s * 2 + (lane >> 5)) * RS + t * 32 + (lane & 31);
+            uint4 h = lds_hi[buf][idx], l = lds_lo[buf][idx];
+            ah[t] = *reinterpret_cast<bf16x8*>(&h);
+            al[t] = *reinterpret_cast<bf16x8*>(&l);
+        }
+        // hi terms of every accumulator first, then the lo terms: consecutive MFMAs never chain on one accumulator
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+                acc[f][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&w[s][f]), ah[t], acc[f][t], 0, 0, 0);
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+                acc[f][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&w[s][f]), al[t], acc[f][t], 0, 0, 0);
+    };
 
-    if (c_begin < c_end) {
-        load_w(c_begin);
+    // Order of memory operations (kept in place by the scheduling fences): per iteration the KS weight reloads
+    // come first, the activation loads last, in the prologue likewise, so at every use the number of younger
+    // loads in flight is the same on the loop's entry edge and on its back edge.
+    if (c_begin < c_end) {   // uniform over the workgroup
+        const int c_last = c_end - 1;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) load_w(c_begin, s);
         load_a(c_begin);
-    }
-    for (int c = c_begin; c < c_end; ++c) {
-        uint4 wcur[KS][NF];
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-#pragma unroll
-            for (int f = 0; f < NF; ++f) wcur[s][f] = wnext[s][f];
-        lds_barrier();  // every wave has finished reading the previous chunk
-        stage_a();
+        stage_a(c_begin, 0);
+        load_a(min(c_begin + 1, c_last));
         lds_barrier();
-        if (c + 1 < c_end) {
-            load_w(c + 1);
-            load_a(c + 1);
+        int buf = 0;
+        for (int c = c_begin; c < c_last; ++c) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                mma_step(buf, s);
+                load_w(c + 1, s);  // slot s is free again: fetch the same k-step of the next chunk
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            stage_a(c + 1, buf ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_a(min(c + 2, c_last));
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();
+            buf ^= 1;
         }
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            bf16x8 ah[MT], al[MT];
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                int idx = (s * 2 + (lane >> 5)) * RS + t * 32 + (lane & 31);
-                uint4 h = lds_hi[idx], l = lds_lo[idx];
-                ah[t] = *reinterpret_cast<bf16x8*>(&h);
-                al[t] = *reinterpret_cast<bf16x8*>(&l);
-            }
-#pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                bf16x8 w = *reinterpret_cast<bf16x8*>(&wcur[s][f]);
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    acc[f][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, ah[t], acc[f][t], 0, 0, 0);
-                    acc[f][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, al[t], acc[f][t], 0, 0, 0);
-                }
-            }
-        }
+        for (int s = 0; s < KS; ++s) mma_step(buf, s);
     }
 
     // D[i][j]: lane holds column j = lane%32 (an activation row m) and rows i = 8*(r/4) + 4*(lane/32) + r%4
@@ -183,90 +198,111 @@ __global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict_
         for (int t = 0; t < MT; ++t) {
             int m = m0 + t * 32 + (lane & 31);
             if (m >= M) continue;
-            float* yrow = Y + (size_t)m * ldy;
+            // mode 0: y = acc;  1: y += acc (this workgroup is the only writer);  2: slice blockIdx.y of the workspace
+            float* yrow = Y + (mode == 2 ? (size_t)blockIdx.y * part_stride : (size_t)0) + (size_t)m * ldy;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 int n = nb + q * 8;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (n + e < Nreal) {
-                        float v = acc[f][t][q * 4 + e];
-                        if (use_atomic) atomicAdd(yrow + n + e, v);
-                        else yrow[n + e] = v;
+                if (n + 3 < Nreal && (ldy & 3) == 0) {
+                    float4 v = make_float4(acc[f][t][q * 4], acc[f][t][q * 4 + 1], acc[f][t][q * 4 + 2], acc[f][t][q * 4 + 3]);
+                    float4* dst = reinterpret_cast<float4*>(yrow + n);
+                    if (mode == 1) {
+                        float4 o = *dst;
+                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
                     }
+                    *dst = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < Nreal) {
+                            float v = acc[f][t][q * 4 + e];
+                            yrow[n + e] = mode == 1 ? yrow[n + e] + v : v;
+                        }
                 }
             }
         }
     }
 }
 
-struct LinearTuning {
-    int ksplit = 0;   // 0 = heuristic
-    int nf = 0;
-    int target_blocks = 512;
-};
-static LinearTuning tuning() {
-    static LinearTuning t = [] {
-        LinearTuning x;
-        if (const char* e = getenv("CHIRON_LINEAR_KSPLIT")) x.ksplit = atoi(e);
-        if (const char* e = getenv("CHIRON_LINEAR_NF")) x.nf = atoi(e);
-        if (const char* e = getenv("CHIRON_LINEAR_BLOCKS")) x.target_blocks = atoi(e);
-        return x;
-    }();
+// sum of K-slices: y (+)= sum_s part[s]  (used by the single-kernel entry points; inside the decode step the
+// consumers of a projection do this sum themselves)
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part, int ks, size_t stride,
+                                                              int64_t n, float* __restrict__ y, int accumulate) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        float v = accumulate ? y[i] : 0.f;
+        for (int s = 0; s < ks; ++s) v += part[(size_t)s * stride + i];
+        y[i] = v;
+    }
+}
+
+int32_t launch_reduce_partials(const float* part, int ks, int64_t n, float* y, int accumulate, hipStream_t st) {
+    int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    reduce_partials_kernel<<<blocks, 256, 0, st>>>(part, ks, (size_t)n, n, y, accumulate);
+    CHIRON_HIP(hipGetLastError());
+    return CHIRON_OK;
+}
+
+Tuning& tuning() {
+    static Tuning t;
     return t;
 }
 
-template <int MT, int NF, int PRO>
-static void launch_cfg(dim3 grid, hipStream_t st, const Linear& L, const float* A, int lda, int M, float* y, int ldy,
-                       int cps, int use_atomic) {
-    linear_kernel<MT, NF, 4, PRO><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, A, lda, M, y, ldy, cps, use_atomic);
+template <int MT, int NF, int KS>
+static void launch_cfg(int prologue, dim3 grid, hipStream_t st, const Linear& L, const float* A, int lda, int M, float* y,
+                       int ldy, int cps, int mode, size_t part_stride) {
+    if (prologue == PRO_SWIGLU)
+        linear_kernel<MT, NF, KS, PRO_SWIGLU><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode, part_stride);
+    else
+        linear_kernel<MT, NF, KS, PRO_NONE><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode, part_stride);
 }
 
+int linear_max_split() { return 16; }
+
 int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
-                      hipStream_t st) {
+                      float* part, int max_split, int* ksplit_out, hipStream_t st) {
+    if (ksplit_out) *ksplit_out = 1;
     if (M == 0) return CHIRON_OK;
-    if (L.K % 16 != 0) return fail(CHIRON_ERR_SHAPE, "linear: K=%d must be a multiple of 16", L.K);
+    if (L.K % 16 != 0 || L.K < 16) return fail(CHIRON_ERR_SHAPE, "linear: K=%d must be a positive multiple of 16", L.K);
     if (lda % 4 != 0 || ((uintptr_t)A & 15)) return fail(CHIRON_ERR_INVALID_ARG, "linear: input rows must be 16-byte aligned");
-    LinearTuning tn = tuning();
-    constexpr int KS = 4, KC = 16 * KS;
+    const Tuning& tn = tuning();
+    const int KS = tn.linear_kstep == 8 ? 8 : 4, KC = 16 * KS;
     int mt = M > 32 ? 2 : 1;
     int tiles = L.Npad / 32;
-    int nf = tn.nf ? tn.nf : (tiles >= 64 ? 2 : 1);
+    int gz0 = (M + 32 * mt - 1) / (32 * mt);
+    // two tiles per wave halve the LDS traffic per weight byte; one tile per wave when that is what it takes to
+    // give every CU a workgroup and K cannot be sliced (no workspace)
+    int nf = tn.linear_nf ? tn.linear_nf : ((!part && ((tiles + 7) / 8) * gz0 < kNumCU) || tiles < 64 ? 1 : 2);
     // (MT=2, NF=1, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
     if (mt == 2 && prologue == PRO_SWIGLU) nf = 2;
     int gx = (tiles + 4 * nf - 1) / (4 * nf);
     int gz = (M + 32 * mt - 1) / (32 * mt);
     int chunks = (L.K + KC - 1) / KC;
-    int ksplit = tn.ksplit ? tn.ksplit : (tn.target_blocks + gx * gz - 1) / (gx * gz);
+    int ksplit = tn.linear_ksplit ? tn.linear_ksplit : (tn.linear_target_blocks + gx * gz - 1) / (gx * gz);
     if (ksplit > chunks / 2) ksplit = chunks / 2;
+    if (ksplit > max_split) ksplit = max_split;
+    if (!part) ksplit = 1;
     if (ksplit < 1) ksplit = 1;
     int cps = (chunks + ksplit - 1) / ksplit;
     ksplit = (chunks + cps - 1) / cps;  // no empty slices
-    int use_atomic = (ksplit > 1 || accumulate) ? 1 : 0;
-    if (ksplit > 1 && !accumulate) {
-        // partial sums are added into y, so it has to start from zero
-        if (ldy == L.N) {
-            int32_t rc = launch_fill_zero(y, (int64_t)M * L.N, st);
-            if (rc) return rc;
-        } else {
-            for (int m = 0; m < M; ++m) {
-                int32_t rc = launch_fill_zero(y + (size_t)m * ldy, L.N, st);
-                if (rc) return rc;
-            }
-        }
-    }
+    int mode = ksplit > 1 ? 2 : (accumulate ? 1 : 0);
+    float* dst = ksplit > 1 ? part : y;
+    int ldd = ksplit > 1 ? L.N : ldy;
+    size_t part_stride = (size_t)M * L.N;
     dim3 grid(gx, ksplit, gz);
-#define CHIRON_LAUNCH(MT_, NF_)                                                                                   \
-    do {                                                                                                           \
-        if (prologue == PRO_SWIGLU) launch_cfg<MT_, NF_, PRO_SWIGLU>(grid, st, L, A, lda, M, y, ldy, cps, use_atomic); \
-        else launch_cfg<MT_, NF_, PRO_NONE>(grid, st, L, A, lda, M, y, ldy, cps, use_atomic);                      \
+#define CHIRON_LAUNCH(MT_, NF_)                                                                                 \
+    do {                                                                                                         \
+        if (KS == 8) launch_cfg<MT_, NF_, 8>(prologue, grid, st, L, A, lda, M, dst, ldd, cps, mode, part_stride); \
+        else launch_cfg<MT_, NF_, 4>(prologue, grid, st, L, A, lda, M, dst, ldd, cps, mode, part_stride);        \
     } while (0)
     if (mt == 1 && nf == 1) CHIRON_LAUNCH(1, 1);
     else if (mt == 1) CHIRON_LAUNCH(1, 2);
-    else if (nf == 1) launch_cfg<2, 1, PRO_NONE>(grid, st, L, A, lda, M, y, ldy, cps, use_atomic);
-    else CHIRON_LAUNCH(2, 2);
+    else if (nf == 1) {
+        if (KS == 8) linear_kernel<2, 1, 8, PRO_NONE><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, dst, ldd, cps, mode, part_stride);
+        else linear_kernel<2, 1, 4, PRO_NONE><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, dst, ldd, cps, mode, part_stride);
+    } else CHIRON_LAUNCH(2, 2);
 #undef CHIRON_LAUNCH
     CHIRON_HIP(hipGetLastError());
+    if (ksplit_out) *ksplit_out = ksplit;
     return CHIRON_OK;
 }
 
