@@ -69,31 +69,14 @@ def cpu_baseline(wl, sample, gpu_logits):
     import numpy as np
     sys.path.insert(0, os.path.join(ROOT, "oracle"))
     import chiron_oracle as orc
-    from paper_2501_08090_amd import inputs as I
-    m = wl.m
-    cfg = orc.make_config(m, orc.BF16, orc.BF16)
-    lens = wl.lens[sample]
-    need = I.pages_needed(lens)
-    bt = np.full((len(sample), int(need.max())), -1, np.int32)   # compact pool: placement does not change results
-    o = 0
-    for r, c in enumerate(need):
-        bt[r, :c] = np.arange(o, o + c)
-        o += c
-    pool = orc.Pool(cfg, o, np.uint16)
-    seq_idx, pos = I.prefill_index(lens)
-    for l, (k, v) in enumerate(wl.kv_host):
-        kf = (k.astype(np.uint32) << 16).view(np.float32)
-        vf = (v.astype(np.uint32) << 16).view(np.float32)
-        orc.append_kv(pool, l, kf, vf, bt, seq_idx, pos)
-    t0 = time.perf_counter()
-    logits, _ = orc.decode_step(cfg, wl.w_host, pool, bt, lens, wl.tok[sample])
-    dt = time.perf_counter() - t0
+    import sample_step
+    logits, _, _, dt = sample_step.run(wl.m, wl.w_host, wl.kv_host, wl.lens[sample], wl.tok[sample])
     sig = float(logits.std())
     err = float(np.abs(gpu_logits - logits).max() / sig)
     agree = float((gpu_logits.argmax(1) == logits.argmax(1)).mean())
     return dict(value=len(sample) / dt, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
                 sample="requests %d..%d of the batch, all %d layers and the LM head, one step (%.1f s)" % (
-                    sample[0], sample[-1], m["n_layers"], dt),
+                    sample[0], sample[-1], wl.m["n_layers"], dt),
                 seconds=dt), dict(rows=len(sample), max_abs_err_over_sigma=err, argmax_agreement=agree)
 
 
@@ -105,7 +88,7 @@ def main():
     ap.add_argument("--workload", default="llama8b-b64-lognormal800")
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep (prefixes of the batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=8)
+    ap.add_argument("--cpu-sample", type=int, default=32)
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "

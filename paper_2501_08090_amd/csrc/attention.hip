@@ -15,6 +15,7 @@
 // memory, so every wave terminates.
 #include <cmath>
 #include <cstdlib>
+#include <type_traits>
 
 #include "chiron_internal.h"
 #include "device_util.h"
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
         // pages per item: small enough that the list holds several items per wave slot, large enough that
         // the per-item partial result stays a small fraction of the bytes the item reads, and such that
         // the list fits (items <= total/cp + batch).
-        int cp = 16;
+        int cp = 64;
         while (cp > 2 && (int64_t)(total / cp) * n_kv < target_waves) cp >>= 1;
         while (total / cp + batch > cap_items) cp <<= 1;
         if (force_cp > 0 && total / force_cp + batch <= cap_items) cp = force_cp;
@@ -159,11 +160,16 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
         float m_run = -INFINITY, l_run = 0.f;
 
         uint4 kc[NPG][KSTEPS], vc[NPG][KSTEPS], kn[NPG][KSTEPS], vn[NPG][KSTEPS];
-        auto load_group = [&](int pg, uint4 (&kk)[NPG][KSTEPS], uint4 (&vv)[NPG][KSTEPS]) {
+        // page ids are fetched one stage ahead of the tiles they address (scalar loads)
+        int blk_next[NPG];
+        auto fetch_ids = [&](int pg) {
+#pragma unroll
+            for (int u = 0; u < NPG; ++u) blk_next[u] = btrow[min(pg + u, pg1 - 1)];  // past the end: the last page, masked
+        };
+        auto load_group = [&](uint4 (&kk)[NPG][KSTEPS], uint4 (&vv)[NPG][KSTEPS]) {
 #pragma unroll
             for (int u = 0; u < NPG; ++u) {
-                int pgx = min(pg + u, pg1 - 1);  // a page past the item's end re-reads the last one (masked below)
-                int blk = __builtin_amdgcn_readfirstlane(btrow[pgx]);
+                int blk = __builtin_amdgcn_readfirstlane(blk_next[u]);
                 const uint16_t* tile = lbase + ((size_t)blk * n_kv + c) * (2 * tile_elems);
 #pragma unroll
                 for (int s = 0; s < KSTEPS; ++s) {
@@ -172,12 +178,10 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                 }
             }
         };
-
-        load_group(pg0, kc, vc);
-        for (int pg = pg0; pg < pg1; pg += NPG) {
-            if (pg + NPG < pg1) load_group(pg + NPG, kn, vn);
-
-            // scores of this stage: s[u][r] = token (pg+u)*16 + 4*lg + r, head = lane%16
+        // one pipeline stage: scores, online-softmax update, P*V.  TAIL stages may hold slots past the
+        // sequence end or a page past the item's end; inner stages are full and need no masks.
+        auto compute = [&](int pg, auto tail_tag) {
+            constexpr bool TAIL = decltype(tail_tag)::value;
             floatx4 s[NPG];
             float mx = -INFINITY;
 #pragma unroll
@@ -189,15 +193,12 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                     s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<bf16x8*>(&qh[k]), s[u], 0, 0, 0);
                     s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, *reinterpret_cast<bf16x8*>(&ql[k]), s[u], 0, 0, 0);
                 }
-                const int len_eff = (pg + u < pg1) ? len : 0;
-                const int tok0 = (pg + u) * 16 + lg * 4;
+                if (TAIL) {
+                    const int len_eff = (pg + u < pg1) ? len : 0;
+                    const int tok0 = (pg + u) * 16 + lg * 4;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    s[u][r] = (tok0 + r < len_eff) ? s[u][r] : -INFINITY;
-                    mx = fmaxf(mx, s[u][r]);
-                }
-                if ((pg + u + 1) * 16 > len_eff) {
-                    // page holds slots past the end: their V bits may be anything, so clear them
+                    for (int r = 0; r < 4; ++r) s[u][r] = (tok0 + r < len_eff) ? s[u][r] : -INFINITY;
+                    // slots past the end may hold any bits (NaN included): clear their V so that 0 * V stays 0
                     int valid = len_eff - tok0;
                     uint32_t m01 = (valid > 0 ? 0x0000ffffu : 0u) | (valid > 1 ? 0xffff0000u : 0u);
                     uint32_t m23 = (valid > 2 ? 0x0000ffffu : 0u) | (valid > 3 ? 0xffff0000u : 0u);
@@ -206,6 +207,8 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                         vc[u][k].x &= m01; vc[u][k].y &= m23; vc[u][k].z &= m01; vc[u][k].w &= m23;
                     }
                 }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[u][r]);
             }
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -232,11 +235,25 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                     uint2 v0 = make_uint2(vc[u][k].x, vc[u][k].y), v1 = make_uint2(vc[u][k].z, vc[u][k].w);
                     short4v a0 = *reinterpret_cast<short4v*>(&v0), a1 = *reinterpret_cast<short4v*>(&v1);
                     o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0, bh, o[2 * k], 0, 0, 0);
-                    o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0, bl, o[2 * k], 0, 0, 0);
                     o[2 * k + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1, bh, o[2 * k + 1], 0, 0, 0);
+                    o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0, bl, o[2 * k], 0, 0, 0);
                     o[2 * k + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1, bl, o[2 * k + 1], 0, 0, 0);
                 }
             }
+        };
+
+        // The steady loop has no divergent branch and a fixed order of loads (next stage's tiles first, then
+        // this stage's arithmetic), so exactly one stage of loads stays in flight behind the one in use.
+        fetch_ids(pg0);
+        load_group(kc, vc);
+        fetch_ids(pg0 + NPG);
+        int pg = pg0;
+        for (; pg + NPG < pg1; pg += NPG) {
+            load_group(kn, vn);
+            fetch_ids(pg + 2 * NPG);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(pg, std::false_type{});
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < NPG; ++u)
 #pragma unroll
@@ -245,6 +262,7 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                     vc[u][k] = vn[u][k];
                 }
         }
+        compute(pg, std::true_type{});
 
         // each lane group summed its own tokens; combine the four groups
         l_run += __shfl_xor(l_run, 16);
@@ -272,31 +290,51 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restr
                                                           int ldo) {
     constexpr int LANES = D / 4, S = 256 / LANES;
     __shared__ float4 s_num[S][LANES];
-    __shared__ float s_den[S];
+    __shared__ float s_den[S], s_max[S];
     const int i = blockIdx.x, a = blockIdx.y, c = a / G, j = a % G;
     const int sl = threadIdx.x / LANES, ln = threadIdx.x % LANES;
     const int item0 = plan[4 + i], nch = plan[4 + max_batch + i];
-    float M = -INFINITY;
-    for (int ch = 0; ch < nch; ++ch) M = fmaxf(M, part_ml[(((size_t)(item0 + ch) * n_kv + c) * G + j) * 2]);
+    // each slice folds its items with a running maximum, two items' loads in flight at a time
+    float M = -INFINITY, den = 0.f;
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-    float den = 0.f;
-    for (int ch = sl; ch < nch; ch += S) {
-        size_t slot = ((size_t)(item0 + ch) * n_kv + c) * G + j;
-        float wgt = __builtin_amdgcn_exp2f(part_ml[slot * 2] - M);
-        den += wgt * part_ml[slot * 2 + 1];
-        float4 o = *reinterpret_cast<const float4*>(part_o + slot * D + ln * 4);
-        num.x += wgt * o.x; num.y += wgt * o.y; num.z += wgt * o.z; num.w += wgt * o.w;
+    auto fold = [&](float m, float l, float4 o) {
+        float Mn = fmaxf(M, m);
+        float a0 = __builtin_amdgcn_exp2f(M - Mn), b0 = __builtin_amdgcn_exp2f(m - Mn);
+        den = den * a0 + l * b0;
+        num.x = num.x * a0 + o.x * b0; num.y = num.y * a0 + o.y * b0;
+        num.z = num.z * a0 + o.z * b0; num.w = num.w * a0 + o.w * b0;
+        M = Mn;
+    };
+    int ch = sl;
+    for (; ch + S < nch; ch += 2 * S) {
+        size_t s0 = ((size_t)(item0 + ch) * n_kv + c) * G + j, s1 = ((size_t)(item0 + ch + S) * n_kv + c) * G + j;
+        float2 ml0 = *reinterpret_cast<const float2*>(part_ml + s0 * 2), ml1 = *reinterpret_cast<const float2*>(part_ml + s1 * 2);
+        float4 o0 = *reinterpret_cast<const float4*>(part_o + s0 * D + ln * 4);
+        float4 o1 = *reinterpret_cast<const float4*>(part_o + s1 * D + ln * 4);
+        fold(ml0.x, ml0.y, o0);
+        fold(ml1.x, ml1.y, o1);
+    }
+    if (ch < nch) {
+        size_t s0 = ((size_t)(item0 + ch) * n_kv + c) * G + j;
+        float2 ml0 = *reinterpret_cast<const float2*>(part_ml + s0 * 2);
+        fold(ml0.x, ml0.y, *reinterpret_cast<const float4*>(part_o + s0 * D + ln * 4));
     }
     s_num[sl][ln] = num;
-    if (ln == 0) s_den[sl] = den;
+    if (ln == 0) {
+        s_den[sl] = den;
+        s_max[sl] = M;
+    }
     __syncthreads();
     if (sl == 0) {
+        float Mt = -INFINITY;
+        for (int k = 0; k < S; ++k) Mt = fmaxf(Mt, s_max[k]);
         float dsum = 0.f;
         float4 n4 = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int k = 0; k < S; ++k) {
-            dsum += s_den[k];
+            float wk = __builtin_amdgcn_exp2f(s_max[k] - Mt);  // empty slices carry max -inf: weight 0
+            dsum += wk * s_den[k];
             float4 t = s_num[k][ln];
-            n4.x += t.x; n4.y += t.y; n4.z += t.z; n4.w += t.w;
+            n4.x += wk * t.x; n4.y += wk * t.y; n4.z += wk * t.z; n4.w += wk * t.w;
         }
         float inv = 1.0f / dsum;
         *reinterpret_cast<float4*>(out + (size_t)i * ldo + (size_t)a * D + ln * 4) =

@@ -44,7 +44,7 @@ struct Tuning {
     int linear_ksplit = 0;          // forced number of K-slices
     int linear_target_blocks = 256; // K is sliced until the grid has about this many workgroups
     int attn_grid = 0;              // workgroups of the persistent attention grid
-    int attn_target_waves = 8192;   // work items aimed for when choosing pages per item
+    int attn_target_waves = 2048;   // work items aimed for when choosing pages per item
     int attn_chunk_pages = 0;       // forced pages per item
 };
 Tuning& tuning();

@@ -41,28 +41,12 @@ def streamed_params(m):
     return m["n_layers"] * sum(a * b for a, b in s.values()) + m["vocab"] * m["hidden"]
 
 
-def build(name, seed=0, host_seqs=(), host_weights=False, max_batch=None, log=None, gain_jitter=0.0):
-    """Returns a Workload with .model .pool .block_table .seq_lens .tokens (GPU) and .lens .bt .tok (numpy).
-    host_weights / host_seqs additionally fill .w_host (numpy storage arrays) and .kv_host[l] = (K, V) rows of
-    the listed requests, concatenated in the order given."""
-    m, kind, batch, pool_factor = WORKLOADS[name]
-    m = dict(m)
+def build_model(m, seed=0, max_batch=1, max_blocks_per_seq=1, host_weights=False, log=None, gain_jitter=0.0):
+    """Random-init model of shape m on the GPU, loaded layer by layer.  Returns (model, w_host or None)."""
     dev = "cuda"
     say = log or (lambda *a: None)
-    wl = Workload()
-    wl.name, wl.m, wl.batch = name, m, batch
-    wl.lens = I.population(kind, batch, seed)
-    wl.bt, wl.num_blocks = I.make_block_table(wl.lens, seed=seed, pool_factor=pool_factor)
-    wl.tok = I.token_ids(batch, m["vocab"], seed)
-    wl.block_table = torch.from_numpy(wl.bt).to(dev)
-    wl.seq_lens = torch.from_numpy(wl.lens).to(dev)
-    wl.tokens = torch.from_numpy(wl.tok).to(dev)
-    wl.context_tokens = int(wl.lens.astype(np.int64).sum()) + batch  # tokens attended over, incl. the new ones
-
-    model = B.Model(m, max_batch or batch, wl.bt.shape[1])
-    wl.model = model
-    host = host_weights or len(host_seqs) > 0
-    wl.w_host = {n: [] for n in I.LAYER_MATRICES + ("attn_norm", "ffn_norm")} if host else None
+    model = B.Model(m, max_batch, max_blocks_per_seq)
+    w_host = {n: [] for n in I.LAYER_MATRICES + ("attn_norm", "ffn_norm")} if host_weights else None
     shp = I.matrix_shapes(m)
     H = m["hidden"]
 
@@ -75,9 +59,9 @@ def build(name, seed=0, host_seqs=(), host_weights=False, max_batch=None, log=No
         lw = {n: I.normal(shp[n], 0.02, seed, n, l, device=dev) for n in I.LAYER_MATRICES}
         lw["attn_norm"], lw["ffn_norm"] = gain("attn_norm", l), gain("ffn_norm", l)
         model.load_layer(l, **lw)
-        if host:
+        if host_weights:
             for n, t in lw.items():
-                wl.w_host[n].append(I.to_numpy_storage(t))
+                w_host[n].append(I.to_numpy_storage(t))
         torch.cuda.synchronize()
         del lw
         if l % 8 == 7:
@@ -86,12 +70,39 @@ def build(name, seed=0, host_seqs=(), host_weights=False, max_batch=None, log=No
     lm_head = I.normal((m["vocab"], H), 0.02, seed, "lm_head", device=dev)
     fin = gain("final_norm")
     model.load_head(embed, fin, lm_head)
-    if host:
-        wl.w_host.update(embed=I.to_numpy_storage(embed), lm_head=I.to_numpy_storage(lm_head), final_norm=I.to_numpy_storage(fin))
+    if host_weights:
+        w_host.update(embed=I.to_numpy_storage(embed), lm_head=I.to_numpy_storage(lm_head), final_norm=I.to_numpy_storage(fin))
     torch.cuda.synchronize()
-    del embed, lm_head
+    return model, w_host
 
-    wl.pool = B.KVPool(model, num_blocks=wl.num_blocks)
+
+def build(name, seed=0, host_seqs=(), host_weights=False, max_batch=None, log=None, gain_jitter=0.0, model=None,
+          w_host=None, pool_memory=None):
+    """Returns a Workload with .model .pool .block_table .seq_lens .tokens (GPU) and .lens .bt .tok (numpy).
+    host_weights / host_seqs additionally fill .w_host (numpy storage arrays) and .kv_host[l] = (K, V) rows of
+    the listed requests, concatenated in the order given.  An existing model of the same shape (created with a
+    large enough max_batch and max_blocks_per_seq) can be passed in to skip the weight generation."""
+    m, kind, batch, pool_factor = WORKLOADS[name]
+    m = dict(m)
+    dev = "cuda"
+    say = log or (lambda *a: None)
+    wl = Workload()
+    wl.name, wl.m, wl.batch = name, m, batch
+    wl.lens = I.population(kind, batch, seed)
+    mb = model.cfg.max_blocks_per_seq if model is not None else None
+    wl.bt, wl.num_blocks = I.make_block_table(wl.lens, seed=seed, pool_factor=pool_factor, max_blocks=mb)
+    wl.tok = I.token_ids(batch, m["vocab"], seed)
+    wl.block_table = torch.from_numpy(wl.bt).to(dev)
+    wl.seq_lens = torch.from_numpy(wl.lens).to(dev)
+    wl.tokens = torch.from_numpy(wl.tok).to(dev)
+    wl.context_tokens = int(wl.lens.astype(np.int64).sum()) + batch  # tokens attended over, incl. the new ones
+
+    if model is None:
+        model, w_host = build_model(m, seed, max_batch or batch, wl.bt.shape[1], host_weights or len(host_seqs) > 0, log,
+                                    gain_jitter)
+    wl.model, wl.w_host = model, w_host
+
+    wl.pool = B.KVPool(model, num_blocks=wl.num_blocks, memory=pool_memory)
     seq_idx, pos = I.prefill_index(wl.lens)
     total = len(seq_idx)
     starts = np.concatenate([[0], np.cumsum(wl.lens.astype(np.int64))])
