@@ -89,6 +89,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep (prefixes of the batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=32)
+    ap.add_argument("--batch", type=int, default=0, help="time a prefix of the workload's batch instead of all of it")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
@@ -103,10 +104,13 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
 
-    m0, kind, batch, _ = W.WORKLOADS[a.workload]
+    m0, kind, full_batch, _ = W.WORKLOADS[a.workload]
+    batch = min(a.batch, full_batch) if a.batch > 0 else full_batch
     sample = list(range(min(a.cpu_sample, batch))) if not a.no_cpu_baseline else []
     t0 = time.time()
     wl = W.build(a.workload, seed=0, host_seqs=sample, host_weights=bool(sample), log=log)
+    if batch != full_batch:
+        wl.context_tokens = int(wl.lens[:batch].astype(np.int64).sum()) + batch
     log("workload %s built in %.1f s: batch %d, %d context tokens, pool %d pages" % (
         a.workload, time.time() - t0, batch, wl.context_tokens, wl.num_blocks))
     m = wl.m
