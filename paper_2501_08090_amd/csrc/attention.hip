@@ -128,36 +128,27 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
     const int head = lane & 15, lg = lane >> 4;
     const size_t tile_elems = (size_t)16 * D;
 
-    for (int w = blockIdx.x * 4 + wave; w < n_work; w += n_waves) {
+    // item metadata (request, first page, length) is fetched one item ahead
+    int w = blockIdx.x * 4 + wave;
+    int i_nx = 0, pg0_nx = 0, len_nx = 0;
+    if (w < n_work) {
+        i_nx = __builtin_amdgcn_readfirstlane(item_seq[w / n_kv]);
+        pg0_nx = __builtin_amdgcn_readfirstlane(item_pg0[w / n_kv]);
+        len_nx = __builtin_amdgcn_readfirstlane(seq_lens[i_nx]) + len_bias;
+    }
+    for (; w < n_work; w += n_waves) {
         const int it = w / n_kv, c = w - it * n_kv;
-        const int i = __builtin_amdgcn_readfirstlane(item_seq[it]);
-        const int pg0 = __builtin_amdgcn_readfirstlane(item_pg0[it]);
-        const int len = __builtin_amdgcn_readfirstlane(seq_lens[i]) + len_bias;
+        const int i = i_nx, pg0 = pg0_nx, len = len_nx;
         const int npages = (len + kBlockSize - 1) / kBlockSize;
         const int pg1 = min(pg0 + cp, npages);
         const int32_t* btrow = bt + (size_t)i * max_blocks;
         const uint16_t* lbase = p.base + (size_t)layer * (size_t)p.layer_stride;
 
-        // q fragments: operand column = head, 8 consecutive dims per lane group; scaled by log2(e)/sqrt(d)
-        uint4 qh[KSTEPS], ql[KSTEPS];
-#pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            if (head < G) {
-                const float* qp = q + (size_t)i * ldq + (size_t)(c * G + head) * D + s * 32 + lg * 8;
-                float4 a = *reinterpret_cast<const float4*>(qp), b = *reinterpret_cast<const float4*>(qp + 4);
-                split2(a.x * scale_log2e, a.y * scale_log2e, qh[s].x, ql[s].x);
-                split2(a.z * scale_log2e, a.w * scale_log2e, qh[s].y, ql[s].y);
-                split2(b.x * scale_log2e, b.y * scale_log2e, qh[s].z, ql[s].z);
-                split2(b.z * scale_log2e, b.w * scale_log2e, qh[s].w, ql[s].w);
-            } else {
-                qh[s] = ql[s] = make_uint4(0, 0, 0, 0);
-            }
-        }
-
         floatx4 o[D / 16];
 #pragma unroll
         for (int t = 0; t < D / 16; ++t) o[t] = floatx4{0.f, 0.f, 0.f, 0.f};
         float m_run = -INFINITY, l_run = 0.f;
+        uint4 qh[KSTEPS], ql[KSTEPS];  // filled below, after the first tile loads have been issued
 
         uint4 kc[NPG][KSTEPS], vc[NPG][KSTEPS], kn[NPG][KSTEPS], vn[NPG][KSTEPS];
         // page ids are fetched one stage ahead of the tiles they address (scalar loads)
@@ -245,8 +236,31 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
         // The steady loop has no divergent branch and a fixed order of loads (next stage's tiles first, then
         // this stage's arithmetic), so exactly one stage of loads stays in flight behind the one in use.
         fetch_ids(pg0);
-        load_group(kc, vc);
+        load_group(kc, vc);   // the first tiles are on their way before anything else of the item is touched
         fetch_ids(pg0 + NPG);
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            const int wn = w + n_waves;  // next item's metadata, needed only after this item is done
+            if (wn < n_work) {
+                i_nx = __builtin_amdgcn_readfirstlane(item_seq[wn / n_kv]);
+                pg0_nx = __builtin_amdgcn_readfirstlane(item_pg0[wn / n_kv]);
+                len_nx = __builtin_amdgcn_readfirstlane(seq_lens[i_nx]) + len_bias;
+            }
+        }
+        // q fragments: operand column = head, 8 consecutive dims per lane group; scaled by log2(e)/sqrt(d)
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            if (head < G) {
+                const float* qp = q + (size_t)i * ldq + (size_t)(c * G + head) * D + s * 32 + lg * 8;
+                float4 a = *reinterpret_cast<const float4*>(qp), b = *reinterpret_cast<const float4*>(qp + 4);
+                split2(a.x * scale_log2e, a.y * scale_log2e, qh[s].x, ql[s].x);
+                split2(a.z * scale_log2e, a.w * scale_log2e, qh[s].y, ql[s].y);
+                split2(b.x * scale_log2e, b.y * scale_log2e, qh[s].z, ql[s].z);
+                split2(b.z * scale_log2e, b.w * scale_log2e, qh[s].w, ql[s].w);
+            } else {
+                qh[s] = ql[s] = make_uint4(0, 0, 0, 0);
+            }
+        }
         int pg = pg0;
         for (; pg + NPG < pg1; pg += NPG) {
             load_group(kn, vn);
