@@ -53,7 +53,7 @@ int32_t chiron_op_paged_attention(chiron_model *m, const chiron_kvpool *p, int32
                                   void *stream);
 
 /* Performance knobs of the kernels, process-wide (0 restores the built-in heuristic where one exists):
- *   linear_nf (1|2), linear_kstep (4|8), linear_ksplit, linear_target_blocks,
+ *   linear_nf (1|2), linear_mt (1|2|4), linear_xcd_remap (0|1), linear_ksplit, linear_target_blocks,
  *   attn_grid, attn_target_waves, attn_chunk_pages.
  * They change launch shapes only, never results beyond summation order. Unknown keys are an error. */
 int32_t chiron_set_tuning(const char *key, int32_t value);

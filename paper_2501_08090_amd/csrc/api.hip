@@ -512,7 +512,7 @@ int32_t chiron_set_tuning(const char* key, int32_t value) {
     if (!key) return fail(CHIRON_ERR_INVALID_ARG, "key is null");
     Tuning& t = tuning();
     struct { const char* k; int* p; } tab[] = {
-        {"linear_nf", &t.linear_nf}, {"linear_kstep", &t.linear_kstep}, {"linear_ksplit", &t.linear_ksplit},
+        {"linear_nf", &t.linear_nf}, {"linear_mt", &t.linear_mt}, {"linear_xcd_remap", &t.linear_xcd_remap}, {"linear_ksplit", &t.linear_ksplit},
         {"linear_target_blocks", &t.linear_target_blocks}, {"attn_grid", &t.attn_grid},
         {"attn_target_waves", &t.attn_target_waves}, {"attn_chunk_pages", &t.attn_chunk_pages}};
     for (auto& e : tab)

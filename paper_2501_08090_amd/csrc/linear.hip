@@ -48,7 +48,7 @@ template <int MT, int NF, int KS, int PRO>
 __global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict__ Wp, int Npad, int Nreal, int K, int Kpad,
                                                      const float* __restrict__ A, int lda, int M,
                                                      float* __restrict__ Y, int ldy, int chunks_per_split,
-                                                     int mode, size_t part_stride) {
+                                                     int mode, size_t part_stride, int gx, int gy, int gz, int remap) {
     constexpr int MROWS = 32 * MT;
     constexpr int RS = MROWS + 1;      // LDS row stride in 16-byte units (+1 breaks the power-of-two stride)
     constexpr int KG = 2 * KS;         // 8-wide k-groups per chunk
@@ -61,10 +61,18 @@ __global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict_
     __shared__ uint4 lds_lo[2][KG * RS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m0 = blockIdx.z * MROWS;
-    const int tile0 = (blockIdx.x * 4 + wave) * NF;  // first 32-column tile of this wave
+    // Workgroups are dealt to the 8 XCDs round-robin.  The 1-D grid is re-read so that consecutive logical ids
+    // sit on ONE XCD, and the M-tile index varies fastest: the workgroups that stream the same weight tiles for
+    // different rows then share that XCD's L2 instead of each pulling the tile from HBM.
+    const int total = gx * gy * gz;
+    const int per_xcd = (total + 7) / 8;
+    const int logical = remap ? (blockIdx.x % 8) * per_xcd + blockIdx.x / 8 : blockIdx.x;
+    if (logical >= total) return;  // grid is padded to a multiple of 8 (uniform over the workgroup)
+    const int bz = logical % gz, bx = (logical / gz) % gx, by = logical / (gz * gx);
+    const int m0 = bz * MROWS;
+    const int tile0 = (bx * 4 + wave) * NF;  // first 32-column tile of this wave
     const int chunks_total = (K + KC - 1) / KC;
-    const int c_begin = blockIdx.y * chunks_per_split;
+    const int c_begin = by * chunks_per_split;
     int c_end = c_begin + chunks_per_split;
     if (c_end > chunks_total) c_end = chunks_total;
 
@@ -199,7 +207,7 @@ __global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict_
             int m = m0 + t * 32 + (lane & 31);
             if (m >= M) continue;
             // mode 0: y = acc;  1: y += acc (this workgroup is the only writer);  2: slice blockIdx.y of the workspace
-            float* yrow = Y + (mode == 2 ? (size_t)blockIdx.y * part_stride : (size_t)0) + (size_t)m * ldy;
+            float* yrow = Y + (mode == 2 ? (size_t)by * part_stride : (size_t)0) + (size_t)m * ldy;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 int n = nb + q * 8;
@@ -247,13 +255,11 @@ Tuning& tuning() {
     return t;
 }
 
-template <int MT, int NF, int KS>
-static void launch_cfg(int prologue, dim3 grid, hipStream_t st, const Linear& L, const float* A, int lda, int M, float* y,
-                       int ldy, int cps, int mode, size_t part_stride) {
-    if (prologue == PRO_SWIGLU)
-        linear_kernel<MT, NF, KS, PRO_SWIGLU><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode, part_stride);
-    else
-        linear_kernel<MT, NF, KS, PRO_NONE><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode, part_stride);
+template <int MT, int NF, int PRO>
+static void launch_cfg(int nblocks, hipStream_t st, const Linear& L, const float* A, int lda, int M, float* y, int ldy,
+                       int cps, int mode, size_t part_stride, int gx, int gy, int gz) {
+    linear_kernel<MT, NF, 4, PRO><<<nblocks, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode,
+                                                           part_stride, gx, gy, gz, tuning().linear_xcd_remap);
 }
 
 int linear_max_split() { return 16; }
@@ -265,17 +271,17 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     if (L.K % 16 != 0 || L.K < 16) return fail(CHIRON_ERR_SHAPE, "linear: K=%d must be a positive multiple of 16", L.K);
     if (lda % 4 != 0 || ((uintptr_t)A & 15)) return fail(CHIRON_ERR_INVALID_ARG, "linear: input rows must be 16-byte aligned");
     const Tuning& tn = tuning();
-    const int KS = tn.linear_kstep == 8 ? 8 : 4, KC = 16 * KS;
-    int mt = M > 32 ? 2 : 1;
+    constexpr int KC = 64;
+    // rows per workgroup: 32 or 64 (128 exists behind the linear_mt knob; at one wave per SIMD it measured slower)
+    int mt = tn.linear_mt ? tn.linear_mt : (M > 32 ? 2 : 1);
     int tiles = L.Npad / 32;
-    int gz0 = (M + 32 * mt - 1) / (32 * mt);
+    int gz = (M + 32 * mt - 1) / (32 * mt);
     // two tiles per wave halve the LDS traffic per weight byte; one tile per wave when that is what it takes to
     // give every CU a workgroup and K cannot be sliced (no workspace)
-    int nf = tn.linear_nf ? tn.linear_nf : ((!part && ((tiles + 7) / 8) * gz0 < kNumCU) || tiles < 64 ? 1 : 2);
+    int nf = tn.linear_nf ? tn.linear_nf : ((!part && ((tiles + 7) / 8) * gz < kNumCU) || tiles < 64 ? 1 : 2);
     // (MT=2, NF=1, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
-    if (mt == 2 && prologue == PRO_SWIGLU) nf = 2;
+    if (prologue == PRO_SWIGLU) nf = 2;
     int gx = (tiles + 4 * nf - 1) / (4 * nf);
-    int gz = (M + 32 * mt - 1) / (32 * mt);
     int chunks = (L.K + KC - 1) / KC;
     int ksplit = tn.linear_ksplit ? tn.linear_ksplit : (tn.linear_target_blocks + gx * gz - 1) / (gx * gz);
     if (ksplit > chunks / 2) ksplit = chunks / 2;
@@ -288,18 +294,20 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     float* dst = ksplit > 1 ? part : y;
     int ldd = ksplit > 1 ? L.N : ldy;
     size_t part_stride = (size_t)M * L.N;
-    dim3 grid(gx, ksplit, gz);
-#define CHIRON_LAUNCH(MT_, NF_)                                                                                 \
-    do {                                                                                                         \
-        if (KS == 8) launch_cfg<MT_, NF_, 8>(prologue, grid, st, L, A, lda, M, dst, ldd, cps, mode, part_stride); \
-        else launch_cfg<MT_, NF_, 4>(prologue, grid, st, L, A, lda, M, dst, ldd, cps, mode, part_stride);        \
+    int nblocks = (gx * ksplit * gz + 7) / 8 * 8;
+#define CHIRON_LAUNCH(MT_, NF_)                                                                                        \
+    do {                                                                                                                \
+        if (prologue == PRO_SWIGLU)                                                                                     \
+            launch_cfg<MT_, 2, PRO_SWIGLU>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz); \
+        else                                                                                                            \
+            launch_cfg<MT_, NF_, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz); \
     } while (0)
     if (mt == 1 && nf == 1) CHIRON_LAUNCH(1, 1);
     else if (mt == 1) CHIRON_LAUNCH(1, 2);
-    else if (nf == 1) {
-        if (KS == 8) linear_kernel<2, 1, 8, PRO_NONE><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, dst, ldd, cps, mode, part_stride);
-        else linear_kernel<2, 1, 4, PRO_NONE><<<grid, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, dst, ldd, cps, mode, part_stride);
-    } else CHIRON_LAUNCH(2, 2);
+    else if (mt == 2 && nf == 1) CHIRON_LAUNCH(2, 1);
+    else if (mt == 2) CHIRON_LAUNCH(2, 2);
+    else if (nf == 1) CHIRON_LAUNCH(4, 1);
+    else CHIRON_LAUNCH(4, 2);
 #undef CHIRON_LAUNCH
     CHIRON_HIP(hipGetLastError());
     if (ksplit_out) *ksplit_out = ksplit;
