@@ -272,15 +272,19 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     if (lda % 4 != 0 || ((uintptr_t)A & 15)) return fail(CHIRON_ERR_INVALID_ARG, "linear: input rows must be 16-byte aligned");
     const Tuning& tn = tuning();
     constexpr int KC = 64;
-    // rows per workgroup: 32 or 64 (128 exists behind the linear_mt knob; at one wave per SIMD it measured slower)
-    int mt = tn.linear_mt ? tn.linear_mt : (M > 32 ? 2 : 1);
+    // Tile shape.  Up to 64 rows the kernel is HBM-bound: 32- or 64-row tiles, two column tiles per wave (one
+    // when that is what it takes to give every CU a workgroup and K cannot be sliced).  From ~384 rows on it is
+    // matrix-core bound and the 128-row x 4-tile wave shape wins (fewer LDS reads and staging per MFMA), at one
+    // wave per SIMD; in between the 64-row shape measured faster.
+    const bool big = M >= 384;
+    int mt = tn.linear_mt ? tn.linear_mt : (big ? 4 : (M > 32 ? 2 : 1));
     int tiles = L.Npad / 32;
     int gz = (M + 32 * mt - 1) / (32 * mt);
-    // two tiles per wave halve the LDS traffic per weight byte; one tile per wave when that is what it takes to
-    // give every CU a workgroup and K cannot be sliced (no workspace)
-    int nf = tn.linear_nf ? tn.linear_nf : ((!part && ((tiles + 7) / 8) * gz < kNumCU) || tiles < 64 ? 1 : 2);
+    int nf = tn.linear_nf ? tn.linear_nf
+                          : (big && tiles >= 256 ? 4 : ((!part && ((tiles + 7) / 8) * gz < kNumCU) || tiles < 64 ? 1 : 2));
     // (MT=2, NF=1, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
     if (prologue == PRO_SWIGLU) nf = 2;
+    if (nf == 4 && mt == 1) mt = 2;
     int gx = (tiles + 4 * nf - 1) / (4 * nf);
     int chunks = (L.K + KC - 1) / KC;
     int ksplit = tn.linear_ksplit ? tn.linear_ksplit : (tn.linear_target_blocks + gx * gz - 1) / (gx * gz);
@@ -302,7 +306,10 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
         else                                                                                                            \
             launch_cfg<MT_, NF_, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz); \
     } while (0)
-    if (mt == 1 && nf == 1) CHIRON_LAUNCH(1, 1);
+    if (nf == 4 && prologue != PRO_SWIGLU) {
+        if (mt == 4) launch_cfg<4, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+        else launch_cfg<2, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+    } else if (mt == 1 && nf == 1) CHIRON_LAUNCH(1, 1);
     else if (mt == 1) CHIRON_LAUNCH(1, 2);
     else if (mt == 2 && nf == 1) CHIRON_LAUNCH(2, 1);
     else if (mt == 2) CHIRON_LAUNCH(2, 2);
