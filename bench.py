@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep (prefixes of the batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=32)
+    ap.add_argument("--autoscale-slo-ms", type=float, default=0.0,
+                    help="also run the local autoscaler (Alg. 1) closed loop on the measured curve with this ITL SLO")
     ap.add_argument("--batch", type=int, default=0, help="time a prefix of the workload's batch instead of all of it")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -174,6 +176,20 @@ def main():
             log("batch %4d: %.3f ms  %.0f tok/s  (%.1f%% of HBM floor)" % (
                 p["batch"], p["lat_ms_median"], p["tokens_per_s"], 100 * p["frac_of_hbm_floor"]))
         out["sweep"] = pts
+
+    if a.autoscale_slo_ms > 0:
+        # Alg. 1 closed loop: ITL and throughput observed at the current maximum batch size, one update per tick
+        slo, mbs, tput_prev, traj = a.autoscale_slo_ms * 1e-3, 1, 0.0, []
+        for tick in range(64):
+            pt = B.step_latency_profile(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, [mbs], warmup=1, iters=3,
+                                        logits=logits)[0]
+            new, lb = B.local_autoscale_step(pt["lat_ms_median"] * 1e-3, slo, tput_prev, pt["tokens_per_s"], mbs, batch)
+            traj.append(dict(max_batch=mbs, itl_ms=round(pt["lat_ms_median"], 3), tokens_per_s=round(pt["tokens_per_s"], 1),
+                             backpressure=round(lb, 4), next_max_batch=new))
+            log("autoscale tick %2d: batch %4d  ITL %.3f ms  backpressure %.3f -> %d" % (tick, mbs, pt["lat_ms_median"], lb, new))
+            tput_prev = pt["tokens_per_s"] if new > mbs else 0.0   # after a scale-down there is nothing comparable
+            mbs = new
+        out["autoscale"] = dict(itl_slo_ms=a.autoscale_slo_ms, alpha=0.5, trajectory=traj)
 
     if sample:
         log("timing the CPU oracle on %d requests ..." % len(sample))

@@ -172,6 +172,23 @@ int32_t chiron_step_latency_profile(chiron_model *m, chiron_kvpool *p, const int
                                     int32_t n_sizes, int32_t warmup, int32_t iters, float *logits_scratch,
                                     void *stream, chiron_profile_point *out);
 
+/* ---- local autoscaler (Local Autoscaler: Local Backpressure, Batch Size Autoscaling, Alg. 1) ---------------
+ *
+ * One update of an instance's maximum batch size from what the iteration exhibited since the last update:
+ *     LBP = itl / itl_slo                      (latency-based backpressure)
+ *     TBP = tput_prev / tput_curr              (throughput-based backpressure)
+ *     LB  = max(LBP, TBP)                      (local backpressure)
+ *     LB <  1:  MBS <- alpha * (1/LB) * MBS + (1 - alpha) * MBS     (EWMA-weighted proportional growth)
+ *     LB >= 1:  MBS <- MBS / 2
+ * itl_slo is the smallest ITL SLO among the requests running on the instance; the paper uses alpha = 0.5 and
+ * runs the update on every change of the running queue.  Where the paper is silent: tput_prev <= 0 (no previous
+ * observation) makes TBP 0; tput_curr <= 0 or itl <= 0 (nothing observed) leaves *max_batch unchanged; LB == 0
+ * grows straight to the limit; the result is rounded to the nearest integer and clamped to [1, batch_limit].
+ * Host only (plain arithmetic, no device work).  *backpressure_out (optional) receives LB, or -1 when the tick
+ * was skipped. */
+int32_t chiron_local_autoscale_step(double itl, double itl_slo, double tput_prev, double tput_curr, double alpha,
+                                    int32_t batch_limit, int32_t *max_batch, double *backpressure_out);
+
 /* Measurement aid: between _begin and _end every kernel launch of chiron_decode_step on this
  * model is bracketed by HIP events on the step's stream; _end synchronises `stream` and returns,
  * per kernel class, the summed event time and the number of launches since _begin.  (The QKV,

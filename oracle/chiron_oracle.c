@@ -16,7 +16,7 @@
  * bf16 pool are rounded to nearest-even.
  *
  * Every function here is pinned by tests/test_oracle_*.py against closed forms,
- * brute force or library routines; none is "parity unpinned".
+ * brute force, library routines or hand-worked values; none is "parity unpinned".
  */
 #include <math.h>
 #ifdef _OPENMP
@@ -268,6 +268,37 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, void *k_pool, voi
 
     free(h); free(x); free(q); free(k); free(v); free(o); free(t); free(g); free(u); free(idx);
     return 0;
+}
+
+/* ---- local autoscaler --------------------------------------------------------------------- */
+
+/* One pass of the batch-size autoscaling loop (Local Autoscaler, Alg. 1), in the paper's notation:
+ * latency-based backpressure LBP = ITL / ITL SLO, throughput-based backpressure TBP =
+ * Throughput_prev / Throughput_curr, local backpressure = max of the two; below one the maximum
+ * batch size grows to alpha * (1 / backpressure) * MBS + (1 - alpha) * MBS, otherwise it is halved.
+ * Readings where the paper is silent (the same as the library documents): no previous throughput
+ * -> TBP = 0; no current observation -> unchanged; zero backpressure -> the limit; nearest integer,
+ * clamped to [1, limit].  Returns the new maximum batch size; *lb_out receives the backpressure
+ * (-1 if the tick was skipped). */
+int orc_autoscale_step(double itl, double itl_slo, double thr_prev, double thr_curr, double alpha, int limit, int mbs,
+                       double *lb_out) {
+    double LBP, TBP, LB, next;
+    if (lb_out) *lb_out = -1.0;
+    if (!(itl > 0.0) || !(thr_curr > 0.0)) return mbs;
+    LBP = itl / itl_slo;
+    TBP = thr_prev > 0.0 ? thr_prev / thr_curr : 0.0;
+    LB = fmax(LBP, TBP);
+    if (lb_out) *lb_out = LB;
+    if (LB < 1.0) {
+        if (LB > 0.0) next = alpha * (1.0 / LB) * (double)mbs + (1.0 - alpha) * (double)mbs;
+        else next = (double)limit;
+    } else {
+        next = (double)mbs / 2.0;
+    }
+    next = floor(next + 0.5);
+    if (next < 1.0) next = 1.0;
+    if (next > (double)limit) next = (double)limit;
+    return (int)next;
 }
 
 /* threads the parallel loops above will use (reported beside timings) */

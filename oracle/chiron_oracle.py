@@ -209,5 +209,15 @@ def decode_step(cfg, w, pool, block_table, seq_lens, tokens):
     return logits, slots
 
 
+def autoscale_step(itl, itl_slo, thr_prev, thr_curr, alpha, limit, mbs):
+    """-> (new max batch size, local backpressure or -1 if the tick was skipped)"""
+    f = lib().orc_autoscale_step
+    f.restype = C.c_int
+    lb = C.c_double()
+    r = f(C.c_double(itl), C.c_double(itl_slo), C.c_double(thr_prev), C.c_double(thr_curr), C.c_double(alpha),
+          C.c_int(int(limit)), C.c_int(int(mbs)), C.byref(lb))
+    return int(r), lb.value
+
+
 def num_threads():
     return int(lib().orc_num_threads())

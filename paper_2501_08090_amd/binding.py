@@ -21,7 +21,7 @@ SYMBOLS = [
     "chiron_model_create", "chiron_model_load_layer", "chiron_model_load_head", "chiron_model_destroy",
     "chiron_kv_block_bytes", "chiron_kv_pool_create", "chiron_kv_pool_destroy", "chiron_append_kv", "chiron_gather_kv",
     "chiron_decode_step", "chiron_validate_step_inputs", "chiron_check_step_inputs_host", "chiron_step_latency_profile",
-    "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end",
+    "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end", "chiron_local_autoscale_step",
     "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_op_swiglu_linear",
     "chiron_op_rope", "chiron_op_paged_attention", "chiron_set_tuning",
 ]
@@ -210,6 +210,15 @@ def step_latency_profile(model, pool, block_table, seq_lens, tokens, batch_sizes
                                               _ptr(logits, torch.float32), _stream(), out))
     return [dict(batch=p.batch, lat_ms_median=p.lat_ms_median, lat_ms_p99=p.lat_ms_p99, lat_ms_mean=p.lat_ms_mean,
                  tokens_per_s=p.tokens_per_s) for p in out]
+
+
+def local_autoscale_step(itl, itl_slo, tput_prev, tput_curr, max_batch, batch_limit, alpha=0.5):
+    """One update of the maximum batch size (host arithmetic).  -> (new max batch, local backpressure)"""
+    mb = C.c_int32(int(max_batch))
+    lb = C.c_double()
+    _check(load().chiron_local_autoscale_step(C.c_double(itl), C.c_double(itl_slo), C.c_double(tput_prev), C.c_double(tput_curr),
+                                              C.c_double(alpha), C.c_int32(int(batch_limit)), C.byref(mb), C.byref(lb)))
+    return mb.value, lb.value
 
 
 KERNEL_CLASSES = ("qkv", "o", "gateup", "down", "lmhead", "attn", "attn_merge", "rmsnorm", "rope_append", "other")

@@ -1,6 +1,7 @@
 // Host side of the C ABI (include/chiron.h, include/chiron_ops.h): handles, argument checks,
 // weight loading, and the sequence of kernel launches that makes one decode step.
 #include <algorithm>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -506,6 +507,27 @@ int32_t chiron_op_paged_attention(chiron_model* m, const chiron_kvpool* p, int32
                           0, batch, st);
     if (rc) return rc;
     return launch_attn_merge(m->aws, p->d, m->cfg.n_q_heads, batch, out, qn, st);
+}
+
+int32_t chiron_local_autoscale_step(double itl, double itl_slo, double tput_prev, double tput_curr, double alpha,
+                                    int32_t batch_limit, int32_t* max_batch, double* backpressure_out) {
+    if (!max_batch) return fail(CHIRON_ERR_INVALID_ARG, "max_batch is null");
+    if (!(itl_slo > 0.0) || !(alpha >= 0.0 && alpha <= 1.0) || batch_limit < 1 || *max_batch < 1)
+        return fail(CHIRON_ERR_INVALID_ARG, "autoscale: need itl_slo > 0, 0 <= alpha <= 1, batch_limit >= 1, max_batch >= 1");
+    if (backpressure_out) *backpressure_out = -1.0;
+    if (!(itl > 0.0) || !(tput_curr > 0.0)) return CHIRON_OK;  // nothing was observed: keep the batch size
+    const double lbp = itl / itl_slo;
+    const double tbp = tput_prev > 0.0 ? tput_prev / tput_curr : 0.0;
+    const double lb = lbp > tbp ? lbp : tbp;
+    double mbs = (double)*max_batch;
+    if (lb < 1.0) mbs = lb > 0.0 ? alpha * (1.0 / lb) * mbs + (1.0 - alpha) * mbs : (double)batch_limit;
+    else mbs = mbs / 2.0;
+    double r = std::floor(mbs + 0.5);
+    if (r < 1.0) r = 1.0;
+    if (r > (double)batch_limit) r = (double)batch_limit;
+    *max_batch = (int32_t)r;
+    if (backpressure_out) *backpressure_out = lb;
+    return CHIRON_OK;
 }
 
 int32_t chiron_set_tuning(const char* key, int32_t value) {

@@ -95,3 +95,37 @@ def test_8b_batch512_mixed_population(model8b):
 
 def test_8b_batch32_long_context(model8b):
     check_workload("llama8b-b32-long32k", model8b, [0, 31], batches=(8,))
+
+
+def test_local_autoscaler_closed_loop_on_the_mixed_population(model8b):
+    """Alg. 1 driven by the measured curve: ITL = median step latency at the current maximum batch size,
+    throughput = batch / ITL, both from chiron_step_latency_profile on prefixes of the 512-request mixed
+    population.  The SLO is set to the measured latency at batch 128, so the feasible maximum is about 128.
+    Every update must equal the oracle's for the same observations; the trajectory must climb, cross the SLO,
+    halve, and stay in a band around the feasible batch size.  (TBP = prev/curr approaches one whenever the
+    batch grows by a small factor, so growth proceeds in shrinking steps; a tick that did not scale up has no
+    comparable previous throughput for the next one, which passes tput_prev = 0.)"""
+    B, W = _mods()
+    model, w_host = model8b
+    wl = W.build("llama8b-mixed-sweep512", seed=0, model=model, w_host=w_host)
+    prof = lambda b: B.step_latency_profile(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, [b], warmup=1, iters=3)[0]
+    slo = prof(128)["lat_ms_median"] * 1e-3
+    mbs, tput_prev, traj = 1, 0.0, []
+    for tick in range(56):
+        pt = prof(mbs)
+        itl, tput = pt["lat_ms_median"] * 1e-3, pt["tokens_per_s"]
+        new, lb = B.local_autoscale_step(itl, slo, tput_prev, tput, mbs, 512)
+        assert (new, lb) == orc.autoscale_step(itl, slo, tput_prev, tput, 0.5, 512, mbs)
+        traj.append((mbs, round(itl * 1e3, 3), round(lb, 3), new))
+        tput_prev = tput if new > mbs else 0.0
+        mbs = new
+    print("SLO %.3f ms; (batch, itl ms, backpressure, next batch):" % (slo * 1e3), traj, flush=True)
+    assert any(lb >= 1.0 for _, _, lb, _ in traj), "never reached the SLO"
+    assert any(n > b for b, _, _, n in traj) and any(n < b for b, _, _, n in traj)
+    feasible = [b for b, itl, lb, _ in traj if lb < 1.0]
+    assert 96 <= max(feasible) <= 160
+    late = [b for b, _, _, _ in traj[40:]]
+    assert min(late) >= 32 and max(late) <= 256
+    wl.pool.close()
+    del wl
+    torch.cuda.empty_cache()
