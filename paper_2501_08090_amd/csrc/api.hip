@@ -451,11 +451,13 @@ static int32_t op_linear_common(const Linear& L, const float* x, int lda, int M,
                                 hipStream_t st) {
     float* part = nullptr;
     const int msplit = linear_max_split();
-    CHIRON_HIP(hipMallocAsync((void**)&part, (size_t)msplit * M * L.N * sizeof(float), st));
+    // wide outputs (LM head, gate/up) have enough column tiles on their own and are never sliced in the step
+    const bool may_split = L.N <= 16384;
+    if (may_split) CHIRON_HIP(hipMallocAsync((void**)&part, (size_t)msplit * M * L.N * sizeof(float), st));
     int ks = 1;
     int32_t rc = launch_linear(L, x, lda, M, y, L.N, accumulate, prologue, part, msplit, &ks, st);
     if (!rc && ks > 1) rc = launch_reduce_partials(part, ks, (int64_t)M * L.N, y, accumulate, st);
-    (void)hipFreeAsync(part, st);
+    if (part) (void)hipFreeAsync(part, st);
     return rc;
 }
 

@@ -45,7 +45,7 @@ int32_t launch_pack_rows(const uint16_t* src, int rows, int K, int Kpad, uint16_
 // is consumed, chunk c+1 is written to the other buffer and chunk c+2 is on its way from L2 into registers;
 // one barrier per chunk.
 template <int MT, int NF, int KS, int PRO>
-__global__ __launch_bounds__(256) void linear_kernel(const uint16_t* __restrict__ Wp, int Npad, int Nreal, int K, int Kpad,
+__global__ __launch_bounds__(256, (MT * NF <= 8 ? 2 : 1)) void linear_kernel(const uint16_t* __restrict__ Wp, int Npad, int Nreal, int K, int Kpad,
                                                      const float* __restrict__ A, int lda, int M,
                                                      float* __restrict__ Y, int ldy, int chunks_per_split,
                                                      int mode, size_t part_stride, int gx, int gy, int gz, int remap) {
