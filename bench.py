@@ -21,6 +21,27 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/*_hbm_traffic.md), already scaled
+# by what the same counters read for a plain 1 GiB copy.  Valid only for the kernel sources they were taken on:
+# `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
+TRAFFIC = {
+    # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
+}
+
+
+def measured_traffic(workload, kclass):
+    import hashlib
+    ent = TRAFFIC.get((workload, kclass))
+    if not ent:
+        return None
+    src, sha, fetch, write = ent
+    path = os.path.join(ROOT, "paper_2501_08090_amd", "csrc", src)
+    try:
+        cur = hashlib.sha256(open(path, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    return dict(fetch_bytes=fetch, write_bytes=write, total_bytes=fetch + write) if cur == sha else None
+
 
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
@@ -152,6 +173,8 @@ def main():
                       "lmhead": "linear_kernel (LM head)", "attn": "paged_attn_kernel"}[dom]
     roof["avg_us"] = d_us
     roof["algorithmic_bytes_per_launch"] = alg[dom]["bytes"]
+    if roof["bound"] == "hbm" and batch == full_batch:
+        roof["traffic"] = measured_traffic(a.workload, dom)
 
     step_bytes = W.algorithmic_bytes(m, wl.lens, batch)
     out = dict(metric="decode_tokens_per_s", value=round(tokens_per_s, 1), unit="tokens/s", n_gpus=1, steps=a.steps,

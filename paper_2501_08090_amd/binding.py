@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libchiron.so")
+LIB_PATH = os.environ.get("CHIRON_LIB", os.path.join(_HERE, "libchiron.so"))
 
 CHIRON_BF16 = 1
 ERRORS = {0: "OK", -1: "INVALID_ARG", -2: "SHAPE", -3: "BATCH_TOO_LARGE", -4: "BLOCK_TABLE", -5: "OOM", -6: "HIP", -7: "TOKEN"}
