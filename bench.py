@@ -112,6 +112,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=32)
     ap.add_argument("--autoscale-slo-ms", type=float, default=0.0,
                     help="also run the local autoscaler (Alg. 1) closed loop on the measured curve with this ITL SLO")
+    ap.add_argument("--swap", action="store_true", help="also time evicting the longest request's cache to pinned host memory and back")
     ap.add_argument("--batch", type=int, default=0, help="time a prefix of the workload's batch instead of all of it")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -213,6 +214,28 @@ def main():
             tput_prev = pt["tokens_per_s"] if new > mbs else 0.0   # after a scale-down there is nothing comparable
             mbs = new
         out["autoscale"] = dict(itl_slo_ms=a.autoscale_slo_ms, alpha=0.5, trajectory=traj)
+
+    if a.swap:
+        # eviction path: the longest request's pages to pinned host memory and back (kernels write/read the host
+        # buffer directly over PCIe)
+        i = int(np.argmax(wl.lens[:batch]))
+        npg = int((int(wl.lens[i]) + 1 + 15) // 16)
+        nbytes = npg * wl.model.kv_block_bytes()
+        image = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        row = wl.block_table[i].contiguous()
+        res = {}
+        for name, fn in (("swap_out", wl.pool.swap_out), ("swap_in", wl.pool.swap_in)):
+            fn(row, npg, image)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                fn(row, npg, image)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / 5
+            res[name] = dict(ms=round(dt * 1e3, 3), GBps=round(nbytes / dt / 1e9, 2))
+        out["swap"] = dict(request=i, context_tokens=int(wl.lens[i]), pages=npg, bytes=nbytes, target="pinned host memory", **res)
+        log("swap of request %d (%d pages, %.1f MB): out %.2f ms (%.1f GB/s), in %.2f ms (%.1f GB/s)" % (
+            i, npg, nbytes / 1e6, res["swap_out"]["ms"], res["swap_out"]["GBps"], res["swap_in"]["ms"], res["swap_in"]["GBps"]))
 
     if sample:
         log("timing the CPU oracle on %d requests ..." % len(sample))

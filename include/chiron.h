@@ -124,6 +124,19 @@ int32_t chiron_append_kv(chiron_kvpool *p, int32_t layer, const void *k, const v
 int32_t chiron_gather_kv(const chiron_kvpool *p, int32_t layer, const int32_t *block_table_row, int32_t len,
                          void *k_out, void *v_out, void *stream);
 
+/* Eviction support (Design: a mixed instance evicts a batch request when an interactive one arrives, and
+ * saves its KV cache by migrating it to CPU memory so that it can restart fast).
+ * chiron_kv_swap_out copies the first n_pages pages of one request (every layer, K and V) into `image`;
+ * chiron_kv_swap_in copies an image back into the pages listed in block_table_row, which may be other pages
+ * than the ones it came from.  `image` is n_pages * chiron_kv_block_bytes() bytes of device-accessible memory:
+ * device memory or pinned host memory (hipHostMalloc), 16-byte aligned; its byte layout is private and only
+ * meaningful to swap_in on a pool of the same model shape.  Pure copies: a request swapped out and back in
+ * gathers bit-identically.   block_table_row: dev int32 [>= n_pages]. */
+int32_t chiron_kv_swap_out(const chiron_kvpool *p, const int32_t *block_table_row, int32_t n_pages, void *image,
+                           void *stream);
+int32_t chiron_kv_swap_in(chiron_kvpool *p, const int32_t *block_table_row, int32_t n_pages, const void *image,
+                          void *stream);
+
 /* ---- the iteration --------------------------------------------------------------------------- */
 
 /* One decode step for `batch` running requests (Continuous Batching: the batch and its

@@ -161,6 +161,24 @@ void orc_gather_kv(const orc_config *c, const void *k_pool, const void *v_pool, 
     }
 }
 
+/* Page migration (a request evicted to host memory and restored, possibly into other pages): copy the first
+ * n_pages pages of a block-table row, every layer, K then V, between the pool and an image laid out as
+ * [layer][K|V][page j][block_size][n_kv][d] in the pool's storage type.  to_image != 0: pool -> image. */
+void orc_swap(const orc_config *c, void *k_pool, void *v_pool, int64_t num_slots, const int32_t *block_table_row,
+              int n_pages, void *image, int to_image) {
+    size_t es = c->kvdtype == ORC_BF16 ? 2 : 4;
+    size_t page = (size_t)c->block_size * c->n_kv_heads * c->head_dim * es; /* bytes of one page, one layer, K or V */
+    for (int l = 0; l < c->n_layers; ++l)
+        for (int kv = 0; kv < 2; ++kv)
+            for (int j = 0; j < n_pages; ++j) {
+                char *pool = (char *)(kv ? v_pool : k_pool) +
+                             pool_off(c, num_slots, l, (int64_t)block_table_row[j] * c->block_size, 0) * es;
+                char *img = (char *)image + (((size_t)l * 2 + kv) * n_pages + j) * page;
+                if (to_image) memcpy(img, pool, page);
+                else memcpy(pool, img, page);
+            }
+}
+
 /* Decode attention of ONE sequence over tokens 0..len-1 of its paged cache:
  * for q head a (KV head a / G): s_t = q_a . K_t / sqrt(d), P = softmax(s),
  * o_a = sum_t P_t V_t.   q: [n_q, d], out: [n_q, d]. */

@@ -164,6 +164,21 @@ def gather_kv(pool, layer, block_table_row, length):
     return k, v
 
 
+def swap(pool, block_table_row, n_pages, image=None):
+    """image None: swap out and return the image (uint8 array); otherwise swap the image in."""
+    r = _i32(block_table_row)
+    cfg = pool.cfg
+    es = 2 if cfg.kvdtype == BF16 else 4
+    nbytes = cfg.n_layers * 2 * n_pages * cfg.block_size * cfg.n_kv_heads * cfg.head_dim * es
+    out = image is None
+    if out:
+        image = np.zeros(nbytes, np.uint8)
+    assert image.size == nbytes
+    lib().orc_swap(C.byref(cfg), _p(pool.k), _p(pool.v), C.c_int64(pool.num_slots), _p(r), C.c_int(n_pages), _p(image),
+                   C.c_int(1 if out else 0))
+    return image
+
+
 def paged_attention(pool, layer, block_table_row, length, q):
     r = _i32(block_table_row)
     q = _f32(q)

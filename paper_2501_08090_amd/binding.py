@@ -20,6 +20,7 @@ ERRORS = {0: "OK", -1: "INVALID_ARG", -2: "SHAPE", -3: "BATCH_TOO_LARGE", -4: "B
 SYMBOLS = [
     "chiron_model_create", "chiron_model_load_layer", "chiron_model_load_head", "chiron_model_destroy",
     "chiron_kv_block_bytes", "chiron_kv_pool_create", "chiron_kv_pool_destroy", "chiron_append_kv", "chiron_gather_kv",
+    "chiron_kv_swap_out", "chiron_kv_swap_in",
     "chiron_decode_step", "chiron_validate_step_inputs", "chiron_check_step_inputs_host", "chiron_step_latency_profile",
     "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end", "chiron_local_autoscale_step",
     "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_op_swiglu_linear",
@@ -156,6 +157,15 @@ class KVPool:
         _check(load().chiron_gather_kv(self._h, C.c_int32(layer), _ptr(block_table_row, torch.int32), C.c_int32(length),
                                        _ptr(k), _ptr(v), _stream()))
         return k, v
+
+    def swap_out(self, block_table_row, n_pages, image):
+        """image: uint8 tensor of n_pages*block_bytes, on the GPU or in pinned host memory"""
+        _check(load().chiron_kv_swap_out(self._h, _ptr(block_table_row, torch.int32), C.c_int32(int(n_pages)),
+                                         C.c_void_p(image.data_ptr()), _stream()))
+
+    def swap_in(self, block_table_row, n_pages, image):
+        _check(load().chiron_kv_swap_in(self._h, _ptr(block_table_row, torch.int32), C.c_int32(int(n_pages)),
+                                        C.c_void_p(image.data_ptr()), _stream()))
 
     def close(self):
         if self._h:

@@ -246,6 +246,26 @@ int32_t chiron_gather_kv(const chiron_kvpool* p, int32_t layer, const int32_t* b
     return launch_gather_kv(p->d, layer, block_table_row, len, (uint16_t*)k_out, (uint16_t*)v_out, (hipStream_t)stream);
 }
 
+static int32_t swap_common(const chiron_kvpool* p, const int32_t* row, int32_t n_pages, const void* image, int to_image,
+                           void* stream) {
+    if (!p) return fail(CHIRON_ERR_INVALID_ARG, "pool is null");
+    if (n_pages < 0) return fail(CHIRON_ERR_INVALID_ARG, "n_pages is negative");
+    if (n_pages == 0) return CHIRON_OK;
+    if (!row || !image) return fail(CHIRON_ERR_INVALID_ARG, "a pointer argument is null");
+    if ((uintptr_t)image & 15) return fail(CHIRON_ERR_INVALID_ARG, "image must be 16-byte aligned");
+    return launch_swap(p->d, row, n_pages, (uint16_t*)const_cast<void*>(image), to_image, (hipStream_t)stream);
+}
+
+int32_t chiron_kv_swap_out(const chiron_kvpool* p, const int32_t* block_table_row, int32_t n_pages, void* image,
+                           void* stream) {
+    return swap_common(p, block_table_row, n_pages, image, 1, stream);
+}
+
+int32_t chiron_kv_swap_in(chiron_kvpool* p, const int32_t* block_table_row, int32_t n_pages, const void* image,
+                          void* stream) {
+    return swap_common(p, block_table_row, n_pages, image, 0, stream);
+}
+
 // ---- the step ------------------------------------------------------------------------------------------
 static int32_t check_step_args(const chiron_model* m, const chiron_kvpool* p, const int32_t* block_table,
                                const int32_t* seq_lens, const int32_t* tokens, int32_t batch) {

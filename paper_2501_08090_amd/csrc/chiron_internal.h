@@ -84,6 +84,8 @@ int32_t launch_append_kv(const PoolDesc& p, int layer, const uint16_t* k, const 
                          int max_blocks, const int32_t* seq_idx, const int32_t* pos, int64_t n, hipStream_t st);
 int32_t launch_gather_kv(const PoolDesc& p, int layer, const int32_t* bt_row, int len, uint16_t* k_out, uint16_t* v_out,
                          hipStream_t st);
+// page migration: image = [page j][layer][kv head][K tile | V tile]; to_image != 0 copies pool -> image
+int32_t launch_swap(const PoolDesc& p, const int32_t* bt_row, int n_pages, uint16_t* image, int to_image, hipStream_t st);
 // decode-step variant: the fused qkv row [rows, (nq+2nkv)*d] is the sum of ks slices qkv[s] (slice stride
 // rows*ld); q and k are rotated in fp32; q goes to q_out [rows, nq*d]; k, v are rounded to bf16 and written at
 // slot(i, seq_lens[i]).

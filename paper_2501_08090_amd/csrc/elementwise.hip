@@ -229,6 +229,27 @@ int32_t launch_gather_kv(const PoolDesc& p, int layer, const int32_t* bt_row, in
     return CHIRON_OK;
 }
 
+// ---- page migration (eviction to host memory and back): one workgroup per (page, layer), 16-byte copies ------
+__global__ __launch_bounds__(256) void swap_kernel(PoolDesc p, const int32_t* __restrict__ bt_row, uint16_t* image,
+                                                   int to_image) {
+    const int j = blockIdx.x, layer = blockIdx.y;
+    const size_t page_elems = (size_t)p.n_kv * 2 * 16 * p.d;
+    uint4* pool = reinterpret_cast<uint4*>(p.base + (size_t)layer * (size_t)p.layer_stride + (size_t)bt_row[j] * page_elems);
+    uint4* img = reinterpret_cast<uint4*>(image + ((size_t)j * p.n_layers + layer) * page_elems);
+    const int n16 = (int)(page_elems / 8);
+    for (int e = threadIdx.x; e < n16; e += 256) {
+        if (to_image) img[e] = pool[e];
+        else pool[e] = img[e];
+    }
+}
+
+int32_t launch_swap(const PoolDesc& p, const int32_t* bt_row, int n_pages, uint16_t* image, int to_image, hipStream_t st) {
+    if (n_pages == 0) return CHIRON_OK;
+    swap_kernel<<<dim3(n_pages, p.n_layers), 256, 0, st>>>(p, bt_row, image, to_image);
+    CHIRON_HIP(hipGetLastError());
+    return CHIRON_OK;
+}
+
 // ---- decode step: sum the K-slices of the QKV projection, rotate q and k, round k and v to bf16, write them
 // at slot(i, seq_lens[i]).  One wave per (request, head): lane j owns dims j, j+64, ... of the head. ------------
 __global__ __launch_bounds__(64) void rope_append_kernel(PoolDesc p, int layer, const float* __restrict__ qkv, int ks,

@@ -73,6 +73,47 @@ def test_append_overwrites_only_its_slot():
             assert np.array_equal(bits(k), bk) and np.array_equal(bits(v), bv)
 
 
+@pytest.mark.parametrize("where", ["device", "pinned_host"])
+def test_swap_out_in_relocates_a_request_bit_exactly(where):
+    """Eviction to (host) memory and restore into other pages: gathers are bit-identical to the oracle's after the
+    same migration, and the decode step's logits do not change by a single bit (page placement never matters)."""
+    c = make_case(batch=4, seed=15, storage="bf16", pool_factor=3.0)
+    g = gpu_setup(c)
+    opool = fresh_pool(c)
+    before = B().decode_step(g.model, g.pool, g.block_table, g.seq_lens, g.tokens).clone()
+    # the step wrote position L of every request: rebuild the cache so that both sides hold the pre-step state
+    g = gpu_setup(c)
+    i = 3
+    L = int(c.seq_lens[i]); npg = int(I.pages_needed([L])[0])
+    nbytes = npg * g.model.kv_block_bytes()
+    image = (torch.empty(nbytes, dtype=torch.uint8, device="cuda") if where == "device"
+             else torch.empty(nbytes, dtype=torch.uint8, pin_memory=True))
+    row = g.block_table[i].contiguous()
+    g.pool.swap_out(row, npg, image)
+    torch.cuda.synchronize()
+    oimage = orc.swap(opool, c.block_table[i], npg)
+    used = set(c.block_table[c.block_table >= 0].tolist())
+    free = [b for b in range(c.num_blocks) if b not in used][:npg]
+    new_row = np.full_like(c.block_table[i], -1); new_row[:npg] = free[::-1]
+    # poison the old pages on the GPU (through the public append), then restore elsewhere
+    nkv, d = c.m["n_kv_heads"], c.m["head_dim"]
+    junk = torch.full((L, nkv, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    for l in range(c.m["n_layers"]):
+        g.pool.append(l, junk, junk, g.block_table, torch.full((L,), i, dtype=torch.int32, device="cuda"),
+                      torch.arange(L, dtype=torch.int32, device="cuda"))
+    new_row_d = torch.from_numpy(new_row).cuda()
+    g.pool.swap_in(new_row_d, npg, image)
+    orc.swap(opool, new_row, npg, oimage)
+    for l in range(c.m["n_layers"]):
+        k, v = g.pool.gather(l, new_row_d, L)
+        ok, ov = orc.gather_kv(opool, l, new_row, L)
+        assert np.array_equal(bits(k), ok) and np.array_equal(bits(v), ov)
+    bt2 = g.block_table.clone(); bt2[i] = new_row_d
+    after = B().decode_step(g.model, g.pool, bt2, g.seq_lens, g.tokens)
+    assert torch.equal(after, before)
+    assert B().load().chiron_kv_swap_out(g.pool._h, None, 1, None, None) == -1
+
+
 # ---- single kernels -------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("rows,n", [(1, 256), (5, 4096), (3, 8192), (2, 688)])

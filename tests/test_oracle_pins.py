@@ -257,3 +257,35 @@ def test_swiglu_matches_library_silu():
     assert np.allclose(orc.swiglu(g, u), want.numpy(), rtol=1e-6, atol=1e-7)
     assert orc.swiglu(np.zeros(1, np.float32), np.ones(1, np.float32))[0] == 0.0
     assert np.isclose(orc.swiglu(np.array([1.0], np.float32), np.array([2.0], np.float32))[0], 2 / (1 + math.exp(-1)))
+
+
+# ---- page migration ---------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_swap_out_and_in_to_other_pages_is_a_pure_relocation(storage):
+    c = make_case(batch=3, seed=21, storage=storage, pool_factor=3.0)
+    pool = fresh_pool(c)
+    i = 2
+    L = int(c.seq_lens[i]); npg = int(I.pages_needed([L])[0])
+    want = [orc.gather_kv(pool, l, c.block_table[i], L) for l in range(TINY["n_layers"])]
+    others = [[orc.gather_kv(pool, l, c.block_table[r], int(c.seq_lens[r])) for l in range(TINY["n_layers"])] for r in (0, 1)]
+    image = orc.swap(pool, c.block_table[i], npg)
+    # the image holds exactly the request's slots: plain numpy indexing as the independent statement
+    es = image.size // (TINY["n_layers"] * 2 * npg * 16 * TINY["n_kv_heads"] * TINY["head_dim"])
+    img = image.view(np.float32 if es == 4 else np.uint16).reshape(TINY["n_layers"], 2, npg * 16, TINY["n_kv_heads"], TINY["head_dim"])
+    slots = (c.block_table[i][np.arange(npg * 16) // 16].astype(np.int64) * 16 + np.arange(npg * 16) % 16)
+    for l in range(TINY["n_layers"]):
+        assert np.array_equal(img[l, 0], pool.k[l, slots]) and np.array_equal(img[l, 1], pool.v[l, slots])
+    # scribble over the old pages, restore into pages nobody uses
+    pool.k[:, slots] = 77; pool.v[:, slots] = 77
+    used = set(c.block_table[c.block_table >= 0].tolist())
+    free = [b for b in range(c.num_blocks) if b not in used][:npg]
+    assert len(free) == npg
+    new_row = np.full_like(c.block_table[i], -1); new_row[:npg] = free[::-1]
+    orc.swap(pool, new_row, npg, image)
+    for l in range(TINY["n_layers"]):
+        k, v = orc.gather_kv(pool, l, new_row, L)
+        assert np.array_equal(k, want[l][0]) and np.array_equal(v, want[l][1])
+        for n, r in enumerate((0, 1)):     # nobody else moved
+            k, v = orc.gather_kv(pool, l, c.block_table[r], int(c.seq_lens[r]))
+            assert np.array_equal(k, others[n][l][0]) and np.array_equal(v, others[n][l][1])
