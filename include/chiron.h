@@ -156,6 +156,16 @@ int32_t chiron_kv_swap_in(chiron_kvpool *p, const int32_t *block_table_row, int3
 int32_t chiron_decode_step(chiron_model *m, chiron_kvpool *p, const int32_t *block_table, const int32_t *seq_lens,
                            const int32_t *tokens, int32_t batch, float *logits, void *stream);
 
+/* Multi-token step (Evaluation setup: speculative decoding, where the served model verifies several drafted
+ * tokens per iteration; Local Autoscaler: chunked prefill is named as another per-instance option): request i
+ * feeds q_len tokens tokens[i][0..q_len) at positions seq_lens[i] .. seq_lens[i]+q_len-1.  Token t attends
+ * causally over positions 0..seq_lens[i]+t, the K/V of all q_len tokens are written (their pages must be in
+ * the block table), and logits[i][t] are the next-token logits after token t.
+ *   tokens dev int32 [batch, q_len];  logits dev fp32 [batch, q_len, vocab];  batch*q_len <= max_batch.
+ * q_len == 1 is chiron_decode_step.  The step runs as batch*q_len rows that share their request's pages. */
+int32_t chiron_decode_step_multi(chiron_model *m, chiron_kvpool *p, const int32_t *block_table, const int32_t *seq_lens,
+                                 const int32_t *tokens, int32_t batch, int32_t q_len, float *logits, void *stream);
+
 /* Debug aid: copies the index arrays to the host (synchronises `stream`) and checks every
  * entry the step would use: page ids in range, written pages unique, token ids in vocab,
  * lengths within max_blocks_per_seq pages. */

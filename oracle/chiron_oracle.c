@@ -288,6 +288,31 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, void *k_pool, voi
     return 0;
 }
 
+/* Multi-token step: request i feeds q_len tokens at positions seq_lens[i] .. seq_lens[i]+q_len-1; token t
+ * attends causally over positions 0 .. seq_lens[i]+t; all q_len tokens' K/V are written.  Written out as
+ * what it means: the q_len tokens are taken one after the other, each as an ordinary single-token step of
+ * the whole batch at the next position (the cache then holds exactly the earlier tokens of the block).
+ * tokens [batch][q_len], logits [batch][q_len][vocab]. */
+int orc_decode_step_multi(const orc_config *c, const orc_weights *w, void *k_pool, void *v_pool, int64_t num_slots,
+                          const int32_t *block_table, int max_blocks, const int32_t *seq_lens, const int32_t *tokens,
+                          int batch, int q_len, float *logits) {
+    int32_t *lens = (int32_t *)malloc(sizeof(int32_t) * (size_t)(batch ? batch : 1));
+    int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)(batch ? batch : 1));
+    float *lg = (float *)malloc(sizeof(float) * (size_t)(batch ? batch : 1) * c->vocab);
+    if (!lens || !tok || !lg) return -1;
+    for (int t = 0; t < q_len; ++t) {
+        for (int i = 0; i < batch; ++i) {
+            lens[i] = seq_lens[i] + t;
+            tok[i] = tokens[(size_t)i * q_len + t];
+        }
+        if (orc_decode_step(c, w, k_pool, v_pool, num_slots, block_table, max_blocks, lens, tok, batch, lg, NULL)) return -1;
+        for (int i = 0; i < batch; ++i)
+            memcpy(logits + ((size_t)i * q_len + t) * c->vocab, lg + (size_t)i * c->vocab, sizeof(float) * c->vocab);
+    }
+    free(lens); free(tok); free(lg);
+    return 0;
+}
+
 /* ---- local autoscaler --------------------------------------------------------------------- */
 
 /* One pass of the batch-size autoscaling loop (Local Autoscaler, Alg. 1), in the paper's notation:

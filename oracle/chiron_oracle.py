@@ -224,6 +224,20 @@ def decode_step(cfg, w, pool, block_table, seq_lens, tokens):
     return logits, slots
 
 
+def decode_step_multi(cfg, w, pool, block_table, seq_lens, tokens):
+    """tokens [B, T] -> logits [B, T, V]; pool is updated in place (T tokens per request appended)."""
+    ws, keep = _weights_struct(w, cfg.n_layers)
+    bt = _i32(block_table)
+    sl, tk = _i32(seq_lens), _i32(tokens)
+    B, T = tk.shape
+    logits = np.empty((B, T, cfg.vocab), np.float32)
+    rc = lib().orc_decode_step_multi(C.byref(cfg), C.byref(ws), _p(pool.k), _p(pool.v), C.c_int64(pool.num_slots), _p(bt),
+                                     C.c_int(bt.shape[1]), _p(sl), _p(tk), C.c_int(B), C.c_int(T), _p(logits))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    return logits
+
+
 def autoscale_step(itl, itl_slo, thr_prev, thr_curr, alpha, limit, mbs):
     """-> (new max batch size, local backpressure or -1 if the tick was skipped)"""
     f = lib().orc_autoscale_step

@@ -21,7 +21,7 @@ SYMBOLS = [
     "chiron_model_create", "chiron_model_load_layer", "chiron_model_load_head", "chiron_model_destroy",
     "chiron_kv_block_bytes", "chiron_kv_pool_create", "chiron_kv_pool_destroy", "chiron_append_kv", "chiron_gather_kv",
     "chiron_kv_swap_out", "chiron_kv_swap_in",
-    "chiron_decode_step", "chiron_validate_step_inputs", "chiron_check_step_inputs_host", "chiron_step_latency_profile",
+    "chiron_decode_step", "chiron_decode_step_multi", "chiron_validate_step_inputs", "chiron_check_step_inputs_host", "chiron_step_latency_profile",
     "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end", "chiron_local_autoscale_step",
     "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_op_swiglu_linear",
     "chiron_op_rope", "chiron_op_paged_attention", "chiron_set_tuning",
@@ -185,6 +185,17 @@ def decode_step(model, pool, block_table, seq_lens, tokens, logits=None, batch=N
         logits = torch.empty((B, model.cfg.vocab), dtype=torch.float32, device="cuda")
     _check(load().chiron_decode_step(model._h, pool._h, _ptr(block_table, torch.int32), _ptr(seq_lens, torch.int32),
                                      _ptr(tokens, torch.int32), C.c_int32(B), _ptr(logits, torch.float32), _stream()))
+    return logits
+
+
+def decode_step_multi(model, pool, block_table, seq_lens, tokens, logits=None):
+    """tokens [batch, q_len] int32 -> logits [batch, q_len, vocab]"""
+    B, T = tokens.shape
+    if logits is None:
+        logits = torch.empty((B, T, model.cfg.vocab), dtype=torch.float32, device="cuda")
+    _check(load().chiron_decode_step_multi(model._h, pool._h, _ptr(block_table, torch.int32), _ptr(seq_lens, torch.int32),
+                                           _ptr(tokens, torch.int32), C.c_int32(B), C.c_int32(T), _ptr(logits, torch.float32),
+                                           _stream()))
     return logits
 
 

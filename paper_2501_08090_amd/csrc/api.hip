@@ -90,7 +90,7 @@ int32_t chiron_model_destroy(chiron_model* m) {
         (void)hipEventDestroy(t.b);
     }
     linear_free(m->lm);
-    void* bufs[] = {m->attn_norm, m->ffn_norm, m->final_norm, m->embed, m->h, m->x, m->qkvb, m->qb, m->part, m->attn, m->gub,
+    void* bufs[] = {m->attn_norm, m->ffn_norm, m->final_norm, m->embed, m->h, m->x, m->qkvb, m->qb, m->part, m->x_bt, m->x_lens, m->attn, m->gub,
                     m->cos_t, m->sin_t, m->aws.plan, m->aws.part_o, m->aws.part_ml};
     for (void* b : bufs)
         if (b) (void)hipFree(b);
@@ -139,6 +139,8 @@ int32_t chiron_model_create(const chiron_model_config* cfg, chiron_model** out) 
     TRY(dev_alloc((void**)&m->qkvb, (size_t)B * (qn + 2 * kn) * 4));
     TRY(dev_alloc((void**)&m->qb, (size_t)B * qn * 4));
     TRY(dev_alloc((void**)&m->part, (size_t)linear_max_split() * B * std::max(qn + 2 * kn, H) * 4));
+    TRY(dev_alloc((void**)&m->x_bt, (size_t)B * cfg->max_blocks_per_seq * 4));
+    TRY(dev_alloc((void**)&m->x_lens, (size_t)B * 4));
     TRY(dev_alloc((void**)&m->attn, (size_t)B * qn * 4));
     TRY(dev_alloc((void**)&m->gub, (size_t)B * 2 * F * 4));
     TRY(dev_alloc((void**)&m->cos_t, (size_t)B * (d / 2) * 4));
@@ -328,6 +330,25 @@ int32_t chiron_decode_step(chiron_model* m, chiron_kvpool* p, const int32_t* blo
     STEP(CHIRON_K_LMHEAD, launch_linear(m->lm, m->x, H, B, logits, c.vocab, 0, PRO_NONE, nullptr, 1, nullptr, st));
 #undef STEP
     return CHIRON_OK;
+}
+
+int32_t chiron_decode_step_multi(chiron_model* m, chiron_kvpool* p, const int32_t* block_table, const int32_t* seq_lens,
+                                 const int32_t* tokens, int32_t batch, int32_t q_len, float* logits, void* stream) {
+    if (q_len < 1) return fail(CHIRON_ERR_INVALID_ARG, "q_len must be at least 1");
+    if (q_len == 1) return chiron_decode_step(m, p, block_table, seq_lens, tokens, batch, logits, stream);
+    if (batch < 0) return fail(CHIRON_ERR_INVALID_ARG, "batch is negative");
+    if (!m) return fail(CHIRON_ERR_INVALID_ARG, "model or pool is null");
+    if ((int64_t)batch * q_len > m->cfg.max_batch)
+        return fail(CHIRON_ERR_BATCH_TOO_LARGE, "batch*q_len = %lld exceeds max_batch %d", (long long)batch * q_len, m->cfg.max_batch);
+    int32_t rc = check_step_args(m, p, block_table, seq_lens, tokens, batch);
+    if (rc) return rc;
+    if (batch == 0) return CHIRON_OK;
+    // rows (i, t) share request i's pages; row t sees the K/V that rows t' <= t append in the same layer, because
+    // every layer appends all rows before its attention starts
+    rc = launch_expand_rows(block_table, seq_lens, batch, q_len, m->cfg.max_blocks_per_seq, m->x_bt, m->x_lens,
+                            (hipStream_t)stream);
+    if (rc) return rc;
+    return chiron_decode_step(m, p, m->x_bt, m->x_lens, tokens, batch * q_len, logits, stream);
 }
 
 int32_t chiron_check_step_inputs_host(const chiron_model_config* cfg, int32_t num_blocks, int32_t block_size,

@@ -84,6 +84,9 @@ int32_t launch_append_kv(const PoolDesc& p, int layer, const uint16_t* k, const 
                          int max_blocks, const int32_t* seq_idx, const int32_t* pos, int64_t n, hipStream_t st);
 int32_t launch_gather_kv(const PoolDesc& p, int layer, const int32_t* bt_row, int len, uint16_t* k_out, uint16_t* v_out,
                          hipStream_t st);
+// multi-token step: row (i,t) of the expanded batch gets request i's block-table row and length seq_lens[i] + t
+int32_t launch_expand_rows(const int32_t* bt, const int32_t* seq_lens, int batch, int q_len, int max_blocks, int32_t* bt_out,
+                           int32_t* lens_out, hipStream_t st);
 // page migration: image = [page j][layer][kv head][K tile | V tile]; to_image != 0 copies pool -> image
 int32_t launch_swap(const PoolDesc& p, const int32_t* bt_row, int n_pages, uint16_t* image, int to_image, hipStream_t st);
 // decode-step variant: the fused qkv row [rows, (nq+2nkv)*d] is the sum of ks slices qkv[s] (slice stride
@@ -131,6 +134,7 @@ struct chiron_model {
     uint16_t* embed = nullptr;
     // step workspace, sized for max_batch
     float *h = nullptr, *x = nullptr, *qkvb = nullptr, *qb = nullptr, *attn = nullptr, *gub = nullptr;
+    int32_t *x_bt = nullptr, *x_lens = nullptr;  // expanded index arrays of the multi-token step
     float* part = nullptr;  // K-slice workspace of the projections: [max_split][max_batch][max(qkv width, hidden)]
     float *cos_t = nullptr, *sin_t = nullptr;
     chiron::AttnWorkspace aws;

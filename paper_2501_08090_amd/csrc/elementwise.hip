@@ -229,6 +229,23 @@ int32_t launch_gather_kv(const PoolDesc& p, int layer, const int32_t* bt_row, in
     return CHIRON_OK;
 }
 
+// ---- multi-token step: expand [batch] requests x q_len tokens into batch*q_len rows ----------------------
+__global__ __launch_bounds__(256) void expand_rows_kernel(const int32_t* __restrict__ bt, const int32_t* __restrict__ seq_lens,
+                                                          int q_len, int max_blocks, int32_t* __restrict__ bt_out,
+                                                          int32_t* __restrict__ lens_out) {
+    const int r = blockIdx.x, i = r / q_len, t = r % q_len;
+    for (int e = threadIdx.x; e < max_blocks; e += 256) bt_out[(size_t)r * max_blocks + e] = bt[(size_t)i * max_blocks + e];
+    if (threadIdx.x == 0) lens_out[r] = seq_lens[i] + t;
+}
+
+int32_t launch_expand_rows(const int32_t* bt, const int32_t* seq_lens, int batch, int q_len, int max_blocks, int32_t* bt_out,
+                           int32_t* lens_out, hipStream_t st) {
+    if (batch * q_len == 0) return CHIRON_OK;
+    expand_rows_kernel<<<batch * q_len, 256, 0, st>>>(bt, seq_lens, q_len, max_blocks, bt_out, lens_out);
+    CHIRON_HIP(hipGetLastError());
+    return CHIRON_OK;
+}
+
 // ---- page migration (eviction to host memory and back): one workgroup per (page, layer), 16-byte copies ------
 __global__ __launch_bounds__(256) void swap_kernel(PoolDesc p, const int32_t* __restrict__ bt_row, uint16_t* image,
                                                    int to_image) {

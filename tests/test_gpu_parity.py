@@ -285,6 +285,34 @@ def test_decode_step_medium_shape_d128():
     check_logits(got, want, min_agree=0.99)
 
 
+@pytest.mark.parametrize("T", [2, 4])
+def test_multi_token_step(T):
+    """q_len > 1 (speculative-decoding verify shape): causal over the block, all T tokens' K/V appended."""
+    lens = [14, 31, 60, 0, 127]
+    c = make_case(seed=16, storage="bf16", gain_jitter=0.1, seq_lens=lens, pool_factor=3.0)
+    toks = I.token_ids(len(lens) * T, c.m["vocab"], 6).reshape(len(lens), T)
+    bt, nb = I.make_block_table(np.asarray(lens) + T - 1, seed=16, pool_factor=3.0)
+    c.block_table, c.num_blocks = bt, nb
+    g = gpu_setup(c, max_batch=len(lens) * T, poison=True)
+    got = B().decode_step_multi(g.model, g.pool, g.block_table, g.seq_lens, torch.from_numpy(toks).cuda()).cpu().numpy()
+    opool = fresh_pool(c)
+    want = orc.decode_step_multi(c.cfg, c.w, opool, bt, c.seq_lens, toks)
+    assert got.shape == (len(lens), T, c.m["vocab"])
+    check_logits(got.reshape(-1, c.m["vocab"]), want.reshape(-1, c.m["vocab"]), min_agree=1.0)
+    # the T new positions of every request hold the oracle's k, v up to one bf16 ulp; older ones are untouched
+    o = 0
+    for i, L in enumerate(lens):
+        k, v = g.pool.gather(1, g.block_table[i].contiguous(), L + T)
+        ok, ov = orc.gather_kv(opool, 1, bt[i], L + T)
+        assert np.array_equal(bits(k)[:L], ok[:L]) and np.array_equal(bits(v)[:L], ov[:L])
+        fa, fb = bf16_to_f32(bits(k)[L:]), bf16_to_f32(ok[L:])
+        assert np.all(np.abs(fa - fb) <= np.abs(fb) * 2.0 ** -7 + 1e-3 * np.abs(fb).max())
+        o += L
+    with pytest.raises(B().ChironError) as e:
+        B().decode_step_multi(g.model, g.pool, g.block_table, g.seq_lens, torch.zeros((len(lens), T + 1), dtype=torch.int32, device="cuda"))
+    assert e.value.code == -3
+
+
 def test_repeat_step_is_idempotent_and_profile_runs():
     c = make_case(batch=4, seed=6, storage="bf16")
     g, got, want, _ = run_both(c)

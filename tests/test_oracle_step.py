@@ -12,9 +12,10 @@ from helpers import as_f64, fresh_pool, make_case
 from paper_2501_08090_amd import inputs as I
 
 
-def torch_reference_step(c):
-    """Second opinion built only from torch float64 library ops on contiguous per-sequence caches
-    (no paging, no shared code with the oracle).  Returns logits [B,V] float64."""
+def torch_reference_multi(c, tokens):
+    """Second opinion built only from torch float64 library ops on contiguous per-sequence caches (no paging, no
+    shared code with the oracle).  tokens [B, T]: request i feeds tokens[i][t] at position seq_lens[i]+t, every
+    token's k, v joins the request's cache before the next one is taken.  Returns logits [B, T, V] float64."""
     m = c.m
     H, nq, nkv, d, F = m["hidden"], m["n_q_heads"], m["n_kv_heads"], m["head_dim"], m["ffn"]
     t64 = lambda a: torch.from_numpy(as_f64(a))
@@ -23,32 +24,42 @@ def torch_reference_step(c):
     out = []
     starts = np.concatenate([[0], np.cumsum(c.seq_lens)])
     for i in range(c.batch):
-        p = int(c.seq_lens[i])
-        h = W["embed"][int(c.tokens[i])].clone()
-        rot = torch.polar(torch.ones_like(inv_freq), p * inv_freq)
+        p0 = int(c.seq_lens[i])
+        Kc = [t64(c.kv[l][0][starts[i]:starts[i] + p0]) for l in range(m["n_layers"])]     # [p, nkv, d] per layer
+        Vc = [t64(c.kv[l][1][starts[i]:starts[i] + p0]) for l in range(m["n_layers"])]
+        row = []
+        for t in range(tokens.shape[1]):
+            p = p0 + t
+            h = W["embed"][int(tokens[i][t])].clone()
+            rot = torch.polar(torch.ones_like(inv_freq), p * inv_freq)
 
-        def rope(x):  # x [heads, d]
-            z = torch.complex(x[:, :d // 2], x[:, d // 2:]) * rot
-            return torch.cat([z.real, z.imag], dim=1)
+            def rope(x):  # x [heads, d]
+                z = torch.complex(x[:, :d // 2], x[:, d // 2:]) * rot
+                return torch.cat([z.real, z.imag], dim=1)
 
-        for l in range(m["n_layers"]):
-            x = torch.nn.functional.rms_norm(h, (H,), W["attn_norm"][l], m["rms_eps"])
-            q = rope((W["wq"][l] @ x).view(nq, d))
-            k = rope((W["wk"][l] @ x).view(nkv, d))
-            v = (W["wv"][l] @ x).view(nkv, d)
-            if c.storage == "bf16":  # the cache stores bf16
-                k = k.float().to(torch.bfloat16).double(); v = v.float().to(torch.bfloat16).double()
-            Kc = torch.cat([t64(c.kv[l][0][starts[i]:starts[i] + p]), k[None]], 0)     # [p+1, nkv, d]
-            Vc = torch.cat([t64(c.kv[l][1][starts[i]:starts[i] + p]), v[None]], 0)
-            Kh = Kc.permute(1, 0, 2).repeat_interleave(nq // nkv, dim=0)                # [nq, p+1, d]
-            Vh = Vc.permute(1, 0, 2).repeat_interleave(nq // nkv, dim=0)
-            o = torch.nn.functional.scaled_dot_product_attention(q[:, None, :], Kh, Vh)  # [nq,1,d]
-            h = h + W["wo"][l] @ o.reshape(nq * d)
-            x = torch.nn.functional.rms_norm(h, (H,), W["ffn_norm"][l], m["rms_eps"])
-            h = h + W["w_down"][l] @ (torch.nn.functional.silu(W["w_gate"][l] @ x) * (W["w_up"][l] @ x))
-        x = torch.nn.functional.rms_norm(h, (H,), W["final_norm"], m["rms_eps"])
-        out.append(W["lm_head"] @ x)
+            for l in range(m["n_layers"]):
+                x = torch.nn.functional.rms_norm(h, (H,), W["attn_norm"][l], m["rms_eps"])
+                q = rope((W["wq"][l] @ x).view(nq, d))
+                k = rope((W["wk"][l] @ x).view(nkv, d))
+                v = (W["wv"][l] @ x).view(nkv, d)
+                if c.storage == "bf16":  # the cache stores bf16
+                    k = k.float().to(torch.bfloat16).double(); v = v.float().to(torch.bfloat16).double()
+                Kc[l] = torch.cat([Kc[l], k[None]], 0)                                       # [p+1, nkv, d]
+                Vc[l] = torch.cat([Vc[l], v[None]], 0)
+                Kh = Kc[l].permute(1, 0, 2).repeat_interleave(nq // nkv, dim=0)              # [nq, p+1, d]
+                Vh = Vc[l].permute(1, 0, 2).repeat_interleave(nq // nkv, dim=0)
+                o = torch.nn.functional.scaled_dot_product_attention(q[:, None, :], Kh, Vh)  # [nq,1,d]
+                h = h + W["wo"][l] @ o.reshape(nq * d)
+                x = torch.nn.functional.rms_norm(h, (H,), W["ffn_norm"][l], m["rms_eps"])
+                h = h + W["w_down"][l] @ (torch.nn.functional.silu(W["w_gate"][l] @ x) * (W["w_up"][l] @ x))
+            x = torch.nn.functional.rms_norm(h, (H,), W["final_norm"], m["rms_eps"])
+            row.append(W["lm_head"] @ x)
+        out.append(torch.stack(row))
     return torch.stack(out).numpy()
+
+
+def torch_reference_step(c):
+    return torch_reference_multi(c, np.asarray(c.tokens).reshape(-1, 1))[:, 0, :]
 
 
 @pytest.mark.parametrize("storage,jitter", [("f32", 0.0), ("f32", 0.2), ("bf16", 0.2)])
@@ -130,3 +141,28 @@ def test_unused_slots_are_never_read():
     c2 = make_case(batch=3, seed=10)
     l2, _ = orc.decode_step(c2.cfg, c2.w, fresh_pool(c2), c2.block_table, c2.seq_lens, c2.tokens)
     assert np.array_equal(logits, l2)
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_multi_token_step_matches_library_composition_and_sequential_steps(storage):
+    c = make_case(batch=3, seed=11, storage=storage, gain_jitter=0.1, seq_lens=[14, 31, 60], pool_factor=3.0)
+    T = 4
+    toks = I.token_ids(3 * T, c.m["vocab"], 5).reshape(3, T)
+    # room for the T new tokens: extend each row's pages from the pool's unused ones
+    bt, nb = I.make_block_table(np.asarray(c.seq_lens) + T - 1, seed=11, pool_factor=3.0)
+    pool = fresh_pool(c, bt, nb)
+    logits = orc.decode_step_multi(c.cfg, c.w, pool, bt, c.seq_lens, toks)
+    want = torch_reference_multi(c, toks)
+    tol = 2e-5 if storage == "f32" else 3e-3
+    assert np.abs(logits - want).max() <= tol * want.std()
+    assert np.array_equal(logits.argmax(2), want.argmax(2))
+    # the same thing as T ordinary steps issued by a caller that advances seq_lens itself: bit-identical
+    pool2 = fresh_pool(c, bt, nb)
+    for t in range(T):
+        lt, _ = orc.decode_step(c.cfg, c.w, pool2, bt, np.asarray(c.seq_lens) + t, toks[:, t])
+        assert np.array_equal(lt, logits[:, t, :])
+    assert np.array_equal(pool.k, pool2.k) and np.array_equal(pool.v, pool2.v)
+    # causality: the logits of token t do not depend on the tokens after it
+    toks2 = toks.copy(); toks2[:, 2:] = (toks2[:, 2:] + 7) % c.m["vocab"]
+    l2 = orc.decode_step_multi(c.cfg, c.w, fresh_pool(c, bt, nb), bt, c.seq_lens, toks2)
+    assert np.array_equal(l2[:, :2], logits[:, :2]) and not np.array_equal(l2[:, 2:], logits[:, 2:])
