@@ -26,6 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "b39421ddc5687632b9dc740417cb6a1a96ce05ee336a438b163b328c013f9fba", 275616722, 4894455),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "9c39d6c81bec1ad33ef7ed18d9ab07f00e5ce2bd3162ab315a9cd55ad9254f1d", 243392938, 7340032),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "9c39d6c81bec1ad33ef7ed18d9ab07f00e5ce2bd3162ab315a9cd55ad9254f1d", 125033033, 16777217),
 }
 
 
@@ -113,6 +116,9 @@ def main():
     ap.add_argument("--autoscale-slo-ms", type=float, default=0.0,
                     help="also run the local autoscaler (Alg. 1) closed loop on the measured curve with this ITL SLO")
     ap.add_argument("--swap", action="store_true", help="also time evicting the longest request's cache to pinned host memory and back")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known bytes) so that rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE "
+                         "readings of the kernels can be scaled by what the same counter reads for it")
     ap.add_argument("--batch", type=int, default=0, help="time a prefix of the workload's batch instead of all of it")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -139,6 +145,14 @@ def main():
         a.workload, time.time() - t0, batch, wl.context_tokens, wl.num_blocks))
     m = wl.m
     logits = torch.empty((batch, m["vocab"]), dtype=torch.float32, device="cuda")
+
+    if a.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)      # 1 GiB read + 1 GiB written by one copy kernel
+        torch.cuda.synchronize()
+        del src, dst
 
     sec = time_steps(B, wl, batch, a.steps, a.warmup, logits)
     gpu_logits = logits[:len(sample)].cpu().numpy() if sample else None
