@@ -23,6 +23,11 @@ int32_t fail(int32_t code, const char* fmt, ...) {
     return code;
 }
 
+// smallest max_batch for which the model carries the workspace of the large-batch projection kernel
+static constexpr int kBigWorkspaceMinBatch = 128;
+// bf16 elements between consecutive 32-row weight tiles beyond 32*Kpad (see Linear::tstride)
+static constexpr int kTilePad = 0;
+
 static int32_t dev_alloc(void** p, size_t bytes) {
     *p = nullptr;
     hipError_t e = hipMalloc(p, bytes ? bytes : 256);
@@ -40,9 +45,12 @@ static int32_t linear_alloc(Linear& L, int N, int K) {
     L.Npad = (N + 31) / 32 * 32;
     L.Kpad = (K + 127) / 128 * 128;
     L.owned = true;
-    int32_t rc = dev_alloc((void**)&L.w, (size_t)L.Npad * L.Kpad * 2);
+    const int pad = tuning().linear_tile_pad;
+    L.tstride = (size_t)32 * L.Kpad + (size_t)(pad < 0 ? kTilePad : pad / 8 * 8);
+    const size_t bytes = (size_t)(L.Npad / 32) * L.tstride * 2;
+    int32_t rc = dev_alloc((void**)&L.w, bytes);
     if (rc) return rc;
-    if (L.Npad != N || L.Kpad != K) CHIRON_HIP(hipMemset(L.w, 0, (size_t)L.Npad * L.Kpad * 2));
+    if (L.Npad != N || L.Kpad != K) CHIRON_HIP(hipMemset(L.w, 0, bytes));
     return CHIRON_OK;
 }
 
@@ -90,7 +98,7 @@ int32_t chiron_model_destroy(chiron_model* m) {
         (void)hipEventDestroy(t.b);
     }
     linear_free(m->lm);
-    void* bufs[] = {m->attn_norm, m->ffn_norm, m->final_norm, m->embed, m->h, m->x, m->qkvb, m->qb, m->part, m->x_bt, m->x_lens, m->attn, m->gub,
+    void* bufs[] = {m->attn_norm, m->ffn_norm, m->final_norm, m->embed, m->h, m->x, m->qkvb, m->qb, m->part, m->asplit, m->x_bt, m->x_lens, m->attn, m->gub,
                     m->cos_t, m->sin_t, m->aws.plan, m->aws.part_o, m->aws.part_ml};
     for (void* b : bufs)
         if (b) (void)hipFree(b);
@@ -139,6 +147,10 @@ int32_t chiron_model_create(const chiron_model_config* cfg, chiron_model** out) 
     TRY(dev_alloc((void**)&m->qkvb, (size_t)B * (qn + 2 * kn) * 4));
     TRY(dev_alloc((void**)&m->qb, (size_t)B * qn * 4));
     TRY(dev_alloc((void**)&m->part, (size_t)linear_max_split() * B * std::max(qn + 2 * kn, H) * 4));
+    if (B >= kBigWorkspaceMinBatch) {
+        const size_t kmax = (size_t)(std::max(std::max(F, H), qn) + 127) / 128 * 128;
+        TRY(dev_alloc((void**)&m->asplit, 2 * linear_big_split_elems(B, (int)kmax) * 2));
+    }
     TRY(dev_alloc((void**)&m->x_bt, (size_t)B * cfg->max_blocks_per_seq * 4));
     TRY(dev_alloc((void**)&m->x_lens, (size_t)B * 4));
     TRY(dev_alloc((void**)&m->attn, (size_t)B * qn * 4));
@@ -166,13 +178,13 @@ int32_t chiron_model_load_layer(chiron_model* m, int32_t layer, const chiron_lay
     const int H = c.hidden, d = c.head_dim, F = c.ffn, qn = c.n_q_heads * d, kn = c.n_kv_heads * d;
     int32_t rc;
     // fused QKV: rows [q | k | v]; fused gate/up: rows [gate | up]
-    if ((rc = launch_pack_rows((const uint16_t*)w->wq, qn, H, m->qkv[layer].Kpad, m->qkv[layer].w, 0, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->wk, kn, H, m->qkv[layer].Kpad, m->qkv[layer].w, qn, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->wv, kn, H, m->qkv[layer].Kpad, m->qkv[layer].w, qn + kn, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->wo, H, qn, m->wo[layer].Kpad, m->wo[layer].w, 0, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->w_gate, F, H, m->gu[layer].Kpad, m->gu[layer].w, 0, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->w_up, F, H, m->gu[layer].Kpad, m->gu[layer].w, F, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->w_down, H, F, m->down[layer].Kpad, m->down[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wq, qn, H, m->qkv[layer].tstride, m->qkv[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wk, kn, H, m->qkv[layer].tstride, m->qkv[layer].w, qn, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wv, kn, H, m->qkv[layer].tstride, m->qkv[layer].w, qn + kn, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->wo, H, qn, m->wo[layer].tstride, m->wo[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_gate, F, H, m->gu[layer].tstride, m->gu[layer].w, 0, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_up, F, H, m->gu[layer].tstride, m->gu[layer].w, F, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_down, H, F, m->down[layer].tstride, m->down[layer].w, 0, st))) return rc;
     CHIRON_HIP(hipMemcpyAsync(m->attn_norm + (size_t)layer * H, w->attn_norm, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
     CHIRON_HIP(hipMemcpyAsync(m->ffn_norm + (size_t)layer * H, w->ffn_norm, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
     return CHIRON_OK;
@@ -185,7 +197,7 @@ int32_t chiron_model_load_head(chiron_model* m, const void* embed, const void* f
     const chiron_model_config& c = m->cfg;
     CHIRON_HIP(hipMemcpyAsync(m->embed, embed, (size_t)c.vocab * c.hidden * 2, hipMemcpyDeviceToDevice, st));
     CHIRON_HIP(hipMemcpyAsync(m->final_norm, final_norm, (size_t)c.hidden * 2, hipMemcpyDeviceToDevice, st));
-    return launch_pack_rows((const uint16_t*)lm_head, c.vocab, c.hidden, m->lm.Kpad, m->lm.w, 0, st);
+    return launch_pack_rows((const uint16_t*)lm_head, c.vocab, c.hidden, m->lm.tstride, m->lm.w, 0, st);
 }
 
 // ---- KV pool -------------------------------------------------------------------------------------------
@@ -313,21 +325,21 @@ int32_t chiron_decode_step(chiron_model* m, chiron_kvpool* p, const int32_t* blo
     for (int l = 0; l < c.n_layers; ++l) {
         // h += (slices of the previous down projection); x = norm(h)
         STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->attn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
-        STEP(CHIRON_K_QKV, launch_linear(m->qkv[l], m->x, H, B, m->qkvb, qn + 2 * kn, 0, PRO_NONE, m->part, msplit, &ks_qkv, st));
+        STEP(CHIRON_K_QKV, launch_linear(m->qkv[l], m->x, H, B, m->qkvb, qn + 2 * kn, 0, PRO_NONE, m->part, msplit, &ks_qkv, m->asplit, st));
         STEP(CHIRON_K_ROPE_APPEND,
              launch_rope_append(p->d, l, ks_qkv > 1 ? m->part : m->qkvb, ks_qkv, c.n_q_heads, m->cos_t, m->sin_t, block_table,
                                 mb, seq_lens, B, m->qb, st));
         STEP(CHIRON_K_ATTN, launch_attn_main(m->aws, p->d, l, m->qb, qn, c.n_q_heads, block_table, mb, seq_lens, 1, B, st));
         STEP(CHIRON_K_ATTN_MERGE, launch_attn_merge(m->aws, p->d, c.n_q_heads, B, m->attn, qn, st));
-        STEP(CHIRON_K_O, launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, m->part, msplit, &ks_res, st));
+        STEP(CHIRON_K_O, launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, m->part, msplit, &ks_res, m->asplit, st));
         if (ks_res == 1) ks_res = 0;  // written straight into h
         STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->ffn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
-        STEP(CHIRON_K_GATEUP, launch_linear(m->gu[l], m->x, H, B, m->gub, 2 * F, 0, PRO_NONE, nullptr, 1, nullptr, st));
-        STEP(CHIRON_K_DOWN, launch_linear(m->down[l], m->gub, 2 * F, B, m->h, H, 1, PRO_SWIGLU, m->part, msplit, &ks_res, st));
+        STEP(CHIRON_K_GATEUP, launch_linear(m->gu[l], m->x, H, B, m->gub, 2 * F, 0, PRO_NONE, nullptr, 1, nullptr, m->asplit, st));
+        STEP(CHIRON_K_DOWN, launch_linear(m->down[l], m->gub, 2 * F, B, m->h, H, 1, PRO_SWIGLU, m->part, msplit, &ks_res, m->asplit, st));
         if (ks_res == 1) ks_res = 0;
     }
     STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->final_norm, B, H, c.rms_eps, m->x, st));
-    STEP(CHIRON_K_LMHEAD, launch_linear(m->lm, m->x, H, B, logits, c.vocab, 0, PRO_NONE, nullptr, 1, nullptr, st));
+    STEP(CHIRON_K_LMHEAD, launch_linear(m->lm, m->x, H, B, logits, c.vocab, 0, PRO_NONE, nullptr, 1, nullptr, m->asplit, st));
 #undef STEP
     return CHIRON_OK;
 }
@@ -468,7 +480,7 @@ int32_t chiron_linear_create(const void* w, int32_t N, int32_t K, void* stream, 
     chiron_linear* l = new (std::nothrow) chiron_linear();
     if (!l) return fail(CHIRON_ERR_OOM, "host allocation failed");
     int32_t rc = linear_alloc(l->L, N, K);
-    if (!rc) rc = launch_pack_rows((const uint16_t*)w, N, K, l->L.Kpad, l->L.w, 0, (hipStream_t)stream);
+    if (!rc) rc = launch_pack_rows((const uint16_t*)w, N, K, l->L.tstride, l->L.w, 0, (hipStream_t)stream);
     if (rc) {
         linear_free(l->L);
         delete l;
@@ -495,8 +507,11 @@ static int32_t op_linear_common(const Linear& L, const float* x, int lda, int M,
     // wide outputs (LM head, gate/up) have enough column tiles on their own and are never sliced in the step
     const bool may_split = L.N <= 16384;
     if (may_split) CHIRON_HIP(hipMallocAsync((void**)&part, (size_t)msplit * M * L.N * sizeof(float), st));
+    uint16_t* asplit = nullptr;
+    if (M >= linear_big_min_rows()) CHIRON_HIP(hipMallocAsync((void**)&asplit, 2 * linear_big_split_elems(M, L.Kpad) * 2, st));
     int ks = 1;
-    int32_t rc = launch_linear(L, x, lda, M, y, L.N, accumulate, prologue, part, msplit, &ks, st);
+    int32_t rc = launch_linear(L, x, lda, M, y, L.N, accumulate, prologue, part, msplit, &ks, asplit, st);
+    if (asplit) (void)hipFreeAsync(asplit, st);
     if (!rc && ks > 1) rc = launch_reduce_partials(part, ks, (int64_t)M * L.N, y, accumulate, st);
     if (part) (void)hipFreeAsync(part, st);
     return rc;
@@ -578,7 +593,7 @@ int32_t chiron_set_tuning(const char* key, int32_t value) {
     Tuning& t = tuning();
     struct { const char* k; int* p; } tab[] = {
         {"linear_nf", &t.linear_nf}, {"linear_mt", &t.linear_mt}, {"linear_xcd_remap", &t.linear_xcd_remap}, {"linear_ksplit", &t.linear_ksplit},
-        {"linear_target_blocks", &t.linear_target_blocks}, {"attn_grid", &t.attn_grid},
+        {"linear_target_blocks", &t.linear_target_blocks}, {"linear_big_min_m", &t.linear_big_min_m}, {"linear_big_all", &t.linear_big_all}, {"linear_tile_pad", &t.linear_tile_pad}, {"attn_grid", &t.attn_grid},
         {"attn_target_waves", &t.attn_target_waves}, {"attn_chunk_pages", &t.attn_chunk_pages}};
     for (auto& e : tab)
         if (!strcmp(e.k, key)) {

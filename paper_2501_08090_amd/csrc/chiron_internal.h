@@ -32,10 +32,12 @@ int32_t fail(int32_t code, const char* fmt, ...);
 struct Linear {
     uint16_t* w = nullptr;  // device, packed and zero-padded
     int N = 0, K = 0, Npad = 0, Kpad = 0;
+    size_t tstride = 0;  // elements from one 32-row tile to the next: 32*Kpad plus a pad that breaks the power of two
     bool owned = false;
 };
 
-enum Prologue { PRO_NONE = 0, PRO_SWIGLU = 1 };
+// PRO_PACKED: the input is already split into its two bf16 terms and tiled (see linear_big.hip)
+enum Prologue { PRO_NONE = 0, PRO_SWIGLU = 1, PRO_PACKED = 2 };
 
 // Performance knobs (0 = built-in heuristic); see chiron_set_tuning.
 struct Tuning {
@@ -44,6 +46,9 @@ struct Tuning {
     int linear_xcd_remap = 1;       // deal logical workgroup ids XCD by XCD (M-tiles of one weight tile share an L2)
     int linear_ksplit = 0;          // forced number of K-slices
     int linear_target_blocks = 256; // K is sliced until the grid has about this many workgroups
+    int linear_big_min_m = 0;       // rows from which the input is pre-split into tiled bf16 terms (0 = built-in, <0 = never)
+    int linear_tile_pad = -1;       // pad between weight tiles in bf16 elements, read when a matrix is packed (-1 = built-in)
+    int linear_big_all = 0;         // 1: pre-split every projection's input from that row count on, not only the SwiGLU one
     int attn_grid = 0;              // workgroups of the persistent attention grid
     int attn_target_waves = 2048;   // work items aimed for when choosing pages per item
     int attn_chunk_pages = 0;       // forced pages per item
@@ -54,11 +59,17 @@ Tuning& tuning();
 // If the launch slices K (only when `part` is given; at most max_split slices), slice s stores its partial product
 // at part[s][M][N] and *ksplit_out = number of slices: the caller's consumer adds them up.  Otherwise the result
 // goes to y (y += if accumulate) and *ksplit_out = 1.
+// `asplit` (optional) is a workspace of 2 * linear_big_split_elems(M, L.Kpad) bf16 values: with it, launches of many
+// rows first store the two bf16 terms of A there in tile order (launch_linear_big) and multiply from those.
 int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
-                      float* part, int max_split, int* ksplit_out, hipStream_t st);
+                      float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st);
+int32_t launch_linear_big(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
+                          float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st);
+size_t linear_big_split_elems(int M, int Kpad);
+int linear_big_min_rows();
 int linear_max_split();
 int32_t launch_reduce_partials(const float* part, int ks, int64_t n, float* y, int accumulate, hipStream_t st);
-int32_t launch_pack_rows(const uint16_t* src, int rows, int K, int Kpad, uint16_t* dst_packed, int row_offset,
+int32_t launch_pack_rows(const uint16_t* src, int rows, int K, size_t tstride, uint16_t* dst_packed, int row_offset,
                          hipStream_t st);
 
 // ---- elementwise / indexing kernels ---------------------------------------------------------------
@@ -136,6 +147,7 @@ struct chiron_model {
     float *h = nullptr, *x = nullptr, *qkvb = nullptr, *qb = nullptr, *attn = nullptr, *gub = nullptr;
     int32_t *x_bt = nullptr, *x_lens = nullptr;  // expanded index arrays of the multi-token step
     float* part = nullptr;  // K-slice workspace of the projections: [max_split][max_batch][max(qkv width, hidden)]
+    uint16_t* asplit = nullptr;  // hi and lo bf16 terms of a projection's input in tile order (large batches only)
     float *cos_t = nullptr, *sin_t = nullptr;
     chiron::AttnWorkspace aws;
     // optional per-kernel event timing of decode steps

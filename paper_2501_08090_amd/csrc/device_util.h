@@ -45,4 +45,15 @@ __device__ __forceinline__ float wave_sum(float v) {
 // flight (weight prefetch) stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// 16 bytes per lane straight from global memory into LDS: lane l's piece lands at lds_addr + 16*l (lds_addr is
+// the wave-uniform byte address inside the workgroup's LDS).  Written as assembly on purpose: the compiler makes
+// every later LDS read wait for all outstanding copies of this kind, which would undo the overlap; the caller
+// waits itself (s_waitcnt vmcnt, then a barrier) before anyone reads the destination.
+__device__ __forceinline__ void global_to_lds_16(const void* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
 }  // namespace chiron

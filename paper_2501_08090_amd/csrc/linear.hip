@@ -8,6 +8,7 @@
 // one K-slice each slice stores its partial product in a workspace [slice][M][N]; the kernel that
 // consumes the projection (residual add + RMSNorm, or RoPE) sums the slices while it reads them,
 // in a fixed order, so results are reproducible run to run.
+#include <climits>
 #include <cstdlib>
 
 #include "chiron_internal.h"
@@ -16,24 +17,24 @@
 namespace chiron {
 
 // ---- weight repacking -------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void pack_rows_kernel(const uint16_t* __restrict__ src, int rows, int K, int Kpad,
+__global__ __launch_bounds__(256) void pack_rows_kernel(const uint16_t* __restrict__ src, int rows, int K, size_t tstride,
                                                         uint16_t* __restrict__ dst, int row_offset) {
-    int kgroups = K / 8, pgroups = Kpad / 8;
+    int kgroups = K / 8;
     int64_t total = (int64_t)rows * kgroups;
     for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
         int r = (int)(t / kgroups), kg = (int)(t % kgroups);
         int n = r + row_offset;
         uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)r * K + (size_t)kg * 8);
-        *reinterpret_cast<uint4*>(dst + ((size_t)(n / 32) * pgroups + kg) * 256 + (size_t)(n % 32) * 8) = v;
+        *reinterpret_cast<uint4*>(dst + (size_t)(n / 32) * tstride + (size_t)kg * 256 + (size_t)(n % 32) * 8) = v;
     }
 }
 
-int32_t launch_pack_rows(const uint16_t* src, int rows, int K, int Kpad, uint16_t* dst_packed, int row_offset,
+int32_t launch_pack_rows(const uint16_t* src, int rows, int K, size_t tstride, uint16_t* dst_packed, int row_offset,
                          hipStream_t st) {
     if (rows == 0) return CHIRON_OK;
     int64_t total = (int64_t)rows * (K / 8);
     int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
-    pack_rows_kernel<<<blocks, 256, 0, st>>>(src, rows, K, Kpad, dst_packed, row_offset);
+    pack_rows_kernel<<<blocks, 256, 0, st>>>(src, rows, K, tstride, dst_packed, row_offset);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -45,7 +46,7 @@ int32_t launch_pack_rows(const uint16_t* src, int rows, int K, int Kpad, uint16_
 // is consumed, chunk c+1 is written to the other buffer and chunk c+2 is on its way from L2 into registers;
 // one barrier per chunk.
 template <int MT, int NF, int KS, int PRO>
-__global__ __launch_bounds__(256, (MT * NF <= 8 ? 2 : 1)) void linear_kernel(const uint16_t* __restrict__ Wp, int Npad, int Nreal, int K, int Kpad,
+__global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE) ? 2 : 1)) void linear_kernel(const uint16_t* __restrict__ Wp, size_t tstride, int Npad, int Nreal, int K, int Kpad,
                                                      const float* __restrict__ A, int lda, int M,
                                                      float* __restrict__ Y, int ldy, int chunks_per_split,
                                                      int mode, size_t part_stride, int gx, int gy, int gz, int remap) {
@@ -85,8 +86,12 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 ? 2 : 1)) void linear_kernel(con
             for (int r = 0; r < 16; ++r) acc[f][t][r] = 0.f;
 
     uint4 w[KS][NF];
-    float4 areg[TPT][2];
+    float4 areg[TPT][2];  // PRO_PACKED: the hi and lo pieces as raw bits
     float4 ureg[PRO == PRO_SWIGLU ? TPT : 1][2];
+    // PRO_PACKED: A points at the hi terms in 32-row x 8-k tile order, the lo terms follow them
+    const int mtiles_all = (M + 31) / 32;
+    const float4* Ahi = reinterpret_cast<const float4*>(A);
+    const float4* Alo = Ahi + (size_t)mtiles_all * 32 * (Kpad / 8);
 
     // The loop body holds no divergent branch: every load is unconditional on a clamped address (the packed
     // weights are zero-padded in K to a whole chunk, out-of-range activation rows/columns are zeroed by a
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 ? 2 : 1)) void linear_kernel(con
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
         int tile = min(tile0 + f, Npad / 32 - 1);  // a wave past the last tile recomputes it; its stores are masked
-        wp[f] = Wp + ((size_t)tile * kgroups + (lane >> 5)) * 256 + (lane & 31) * 8;
+        wp[f] = Wp + (size_t)tile * tstride + (lane >> 5) * 256 + (lane & 31) * 8;
     }
     auto load_w = [&](int c, int s) {
         size_t off = (size_t)(c * KC + s * 16) * 32;
@@ -105,6 +110,9 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 ? 2 : 1)) void linear_kernel(con
     };
     auto load_a = [&](int c) {
         int kbase = c * KC;
+        if (PRO == PRO_PACKED) {
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
             int task = tid + i * 256;
@@ -121,6 +129,9 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 ? 2 : 1)) void linear_kernel(con
     };
     auto stage_a = [&](int c, int buf) {
         int kbase = c * KC;
+        if (PRO == PRO_PACKED) {
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
             int task = tid + i * 256;
@@ -143,6 +154,22 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 ? 2 : 1)) void linear_kernel(con
             split2(v[6], v[7], hi.w, lo.w);
             lds_hi[buf][kg * RS + m] = hi;
             lds_lo[buf][kg * RS + m] = lo;
+        }
+    };
+    // PRO_PACKED: chunk c of the pre-split activations goes HBM/L2 -> LDS directly (16 bytes per lane, a wave
+    // fills 64 consecutive rows of one k-group), no registers and no LDS store instructions in between
+    auto dma_a = [&](int c, uint4* dst_hi, uint4* dst_lo) {
+        constexpr int JOBS = KG * (MROWS / 64) * 2;  // (k-group, 64-row half, hi|lo) per chunk
+        static_assert(PRO != PRO_PACKED || (MROWS % 64 == 0 && JOBS % 4 == 0), "packed input needs 64-row halves");
+#pragma unroll
+        for (int j = 0; j < JOBS / 4; ++j) {
+            const int job = wave + 4 * j;
+            const int lo = job & 1, half = (job >> 1) % (MROWS / 64), kg = (job >> 1) / (MROWS / 64);
+            const int m = half * 64 + lane;
+            const size_t idx = ((size_t)min(bz * MT + m / 32, mtiles_all - 1) * kgroups + (c * KG + kg)) * 32 + (m & 31);
+            const float4* g = (lo ? Alo : Ahi) + idx;
+            uint4* l = (lo ? dst_lo : dst_hi) + kg * RS + half * 64;
+            global_to_lds_16(g, __builtin_amdgcn_readfirstlane(lds_address(l)));
         }
     };
     auto mma_step = [&](int buf, int s) {
@@ -170,10 +197,45 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 ? 2 : 1)) void linear_kernel(con
     // Order of memory operations (kept in place by the scheduling fences): per iteration the KS weight reloads
     // come first, the activation loads last, in the prologue likewise, so at every use the number of younger
     // loads in flight is the same on the loop's entry edge and on its back edge.
+    if (PRO == PRO_PACKED) {
+        if (c_begin < c_end) {  // uniform over the workgroup
+            const int c_last = c_end - 1;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                load_w(c_begin, s);
+                __builtin_amdgcn_sched_barrier(0);  // same issue order as in the loop: k-step 0 is the oldest
+            }
+            dma_a(c_begin, lds_hi[0], lds_lo[0]);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            lds_barrier();
+            int buf = 0;
+            for (int c = c_begin; c < c_last; ++c) {
+                // start the copy of chunk c+1 into the idle buffer (last read before the barrier that ended the
+                // previous round), multiply chunk c out of the other one while refilling the weight ring
+                dma_a(c + 1, lds_hi[buf ^ 1], lds_lo[buf ^ 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int s = 0; s < KS; ++s) {
+                    mma_step(buf, s);
+                    load_w(c + 1, s);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // the KS*NF weight loads just issued are younger than the activation copy: let them fly
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KS * NF) : "memory");
+                lds_barrier();
+                buf ^= 1;
+            }
+#pragma unroll
+            for (int s = 0; s < KS; ++s) mma_step(buf, s);
+        }
+    } else
     if (c_begin < c_end) {   // uniform over the workgroup
         const int c_last = c_end - 1;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) load_w(c_begin, s);
+        for (int s = 0; s < KS; ++s) {
+            load_w(c_begin, s);
+            __builtin_amdgcn_sched_barrier(0);  // same issue order as in the loop: k-step 0 is the oldest
+        }
         load_a(c_begin);
         stage_a(c_begin, 0);
         load_a(min(c_begin + 1, c_last));
@@ -258,18 +320,28 @@ Tuning& tuning() {
 template <int MT, int NF, int PRO>
 static void launch_cfg(int nblocks, hipStream_t st, const Linear& L, const float* A, int lda, int M, float* y, int ldy,
                        int cps, int mode, size_t part_stride, int gx, int gy, int gz) {
-    linear_kernel<MT, NF, 4, PRO><<<nblocks, 256, 0, st>>>(L.w, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode,
+    linear_kernel<MT, NF, 4, PRO><<<nblocks, 256, 0, st>>>(L.w, L.tstride, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode,
                                                            part_stride, gx, gy, gz, tuning().linear_xcd_remap);
 }
 
 int linear_max_split() { return 16; }
 
+static constexpr int kBigMinRows = 320;  // rows from which the pre-split path is faster for the SwiGLU projection (measured)
+
+int linear_big_min_rows() {
+    const int v = tuning().linear_big_min_m;
+    return v == 0 ? kBigMinRows : (v < 0 ? INT32_MAX : v);
+}
+
 int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
-                      float* part, int max_split, int* ksplit_out, hipStream_t st) {
+                      float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st) {
     if (ksplit_out) *ksplit_out = 1;
     if (M == 0) return CHIRON_OK;
+    if (asplit && prologue != PRO_PACKED && M >= linear_big_min_rows() && (prologue == PRO_SWIGLU || tuning().linear_big_all))
+        return launch_linear_big(L, A, lda, M, y, ldy, accumulate, prologue, part, max_split, ksplit_out, asplit, st);
     if (L.K % 16 != 0 || L.K < 16) return fail(CHIRON_ERR_SHAPE, "linear: K=%d must be a positive multiple of 16", L.K);
-    if (lda % 4 != 0 || ((uintptr_t)A & 15)) return fail(CHIRON_ERR_INVALID_ARG, "linear: input rows must be 16-byte aligned");
+    if (prologue != PRO_PACKED && (lda % 4 != 0 || ((uintptr_t)A & 15)))
+        return fail(CHIRON_ERR_INVALID_ARG, "linear: input rows must be 16-byte aligned");
     const Tuning& tn = tuning();
     constexpr int KC = 64;
     // Tile shape.  Up to 64 rows the kernel is HBM-bound: 32- or 64-row tiles, two column tiles per wave (one
@@ -284,6 +356,10 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
                           : (big && tiles >= 256 ? 4 : ((!part && ((tiles + 7) / 8) * gz < kNumCU) || tiles < 64 ? 1 : 2));
     // (MT=2, NF=1, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
     if (prologue == PRO_SWIGLU) nf = 2;
+    if (prologue == PRO_PACKED) {  // only the large-batch shapes are built for pre-split input
+        mt = 4;
+        if (nf != 4) nf = 2;
+    }
     if (nf == 4 && mt == 1) mt = 2;
     int gx = (tiles + 4 * nf - 1) / (4 * nf);
     int chunks = (L.K + KC - 1) / KC;
@@ -306,7 +382,10 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
         else                                                                                                            \
             launch_cfg<MT_, NF_, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz); \
     } while (0)
-    if (nf == 4 && prologue != PRO_SWIGLU) {
+    if (prologue == PRO_PACKED) {
+        if (nf == 4) launch_cfg<4, 4, PRO_PACKED>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+        else launch_cfg<4, 2, PRO_PACKED>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+    } else if (nf == 4 && prologue != PRO_SWIGLU) {
         if (mt == 4) launch_cfg<4, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else launch_cfg<2, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
     } else if (mt == 1 && nf == 1) CHIRON_LAUNCH(1, 1);

@@ -160,6 +160,41 @@ def test_swiglu_linear(M, N, K):
     lin.close()
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 512, 256), (300, 1000, 688), (513, 2080, 1040), (97, 96, 64), (640, 4096, 512)])
+def test_linear_large_batch_kernel(M, N, K):
+    """the large-batch path (activations pre-split into tiled bf16 terms, copied straight into LDS), forced at any M"""
+    rng = np.random.default_rng(M * 5 + N * 3 + K)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    W = I.normal((N, K), 0.05, 8, "wb", N, K)
+    print("linear big", M, N, K, flush=True)
+    b = B()
+    b.set_tuning("linear_big_min_m", 1)
+    b.set_tuning("linear_big_all", 1)
+    try:
+        lin = b.Linear(W.cuda())
+        xg = torch.from_numpy(x).cuda()
+        got = lin(xg).cpu().numpy()
+        want = orc.linear(x, I.to_numpy_storage(W))
+        assert rel_err(got, want) <= KERNEL_TOL
+        y0 = rng.standard_normal((M, N)).astype(np.float32)
+        got2 = lin(xg, torch.from_numpy(y0).cuda(), accumulate=True).cpu().numpy()
+        assert rel_err(got2, want + y0) <= KERNEL_TOL
+        lin.close()
+        if K % 2 == 0:  # SwiGLU input: gate | up halves of width K/2
+            Kh = K // 2
+            Wd = I.normal((N, Kh), 0.05, 9, "wbd", N, Kh)
+            if Kh % 16 == 0:
+                lin = b.Linear(Wd.cuda())
+                gu = (x * 2).astype(np.float32)
+                got3 = lin.swiglu(torch.from_numpy(gu).cuda()).cpu().numpy()
+                want3 = orc.linear(orc.swiglu(gu[:, :Kh], gu[:, Kh:]), I.to_numpy_storage(Wd))
+                assert rel_err(got3, want3) <= KERNEL_TOL
+                lin.close()
+    finally:
+        b.set_tuning("linear_big_min_m", 0)
+        b.set_tuning("linear_big_all", 0)
+
+
 def test_rope_large_positions():
     rng = np.random.default_rng(21)
     pos = np.array([0, 1, 17, 4095, 32767, 131071], np.int32)
