@@ -358,7 +358,7 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     if (prologue == PRO_SWIGLU) nf = 2;
     if (prologue == PRO_PACKED) {  // only the large-batch shapes are built for pre-split input
         mt = 4;
-        if (nf != 4) nf = 2;
+        nf = tn.linear_nf ? (tn.linear_nf == 4 ? 4 : 2) : (tiles >= 128 ? 4 : 2);
     }
     if (nf == 4 && mt == 1) mt = 2;
     int gx = (tiles + 4 * nf - 1) / (4 * nf);
