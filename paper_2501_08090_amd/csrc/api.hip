@@ -593,7 +593,7 @@ int32_t chiron_set_tuning(const char* key, int32_t value) {
     Tuning& t = tuning();
     struct { const char* k; int* p; } tab[] = {
         {"linear_nf", &t.linear_nf}, {"linear_mt", &t.linear_mt}, {"linear_xcd_remap", &t.linear_xcd_remap}, {"linear_ksplit", &t.linear_ksplit},
-        {"linear_target_blocks", &t.linear_target_blocks}, {"linear_big_min_m", &t.linear_big_min_m}, {"linear_big_all", &t.linear_big_all}, {"linear_tile_pad", &t.linear_tile_pad}, {"attn_grid", &t.attn_grid},
+        {"linear_target_blocks", &t.linear_target_blocks}, {"linear_big_min_m", &t.linear_big_min_m}, {"linear_big_all", &t.linear_big_all}, {"linear_ks", &t.linear_ks}, {"linear_tile_pad", &t.linear_tile_pad}, {"attn_grid", &t.attn_grid},
         {"attn_target_waves", &t.attn_target_waves}, {"attn_chunk_pages", &t.attn_chunk_pages}};
     for (auto& e : tab)
         if (!strcmp(e.k, key)) {

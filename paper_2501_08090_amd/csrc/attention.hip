@@ -31,9 +31,8 @@ constexpr int kPlanThreads = 1024;
 
 __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __restrict__ plan, int max_batch, int cap_items,
                                                                  const int32_t* __restrict__ seq_lens, int len_bias,
-                                                                 int batch, int n_kv, int target_waves, int force_cp) {
+                                                                 int batch, int n_kv, int slots, int target_waves, int force_cp) {
     __shared__ int scan[kPlanThreads];
-    __shared__ int s_cp;
     int32_t* seq_item0 = plan + 4;
     int32_t* seq_nch = plan + 4 + max_batch;
     int32_t* item_seq = plan + 4 + 2 * max_batch;
@@ -42,28 +41,46 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     const int per = (batch + kPlanThreads - 1) / kPlanThreads;  // requests per thread, contiguous
     const int i0 = tid * per, i1 = min(batch, i0 + per);
 
-    // total pages
+    // block-wide sums over the requests (every thread gets the total)
+    auto block_sum = [&](int v) {
+        __syncthreads();
+        scan[tid] = v;
+        __syncthreads();
+        for (int o = kPlanThreads / 2; o > 0; o >>= 1) {
+            if (tid < o) scan[tid] += scan[tid + o];
+            __syncthreads();
+        }
+        return scan[0];
+    };
+    auto count_items = [&](int cp) {
+        int n = 0;
+        for (int i = i0; i < i1; ++i) n += ((seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize + cp - 1) / cp;
+        return block_sum(n);
+    };
     int pages = 0;
     for (int i = i0; i < i1; ++i) pages += (seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize;
-    scan[tid] = pages;
-    __syncthreads();
-    for (int o = kPlanThreads / 2; o > 0; o >>= 1) {
-        if (tid < o) scan[tid] += scan[tid + o];
-        __syncthreads();
+    const int total = block_sum(pages);
+
+    // Pages per item.  A wave takes items w, w + slots, ...: if the list is only a little longer than the number of
+    // wave slots, a few waves run a second item alone, at latency-bound speed, after everyone else has finished.
+    // So: when one round can hold everything, take the smallest item size that fits one round (all items stream
+    // concurrently); otherwise make the items small enough for at least four rounds, where a ragged last round
+    // costs little, but not so small that the per-item partial result weighs against the bytes the item reads.
+    int cp;
+    if ((int64_t)count_items(64) * n_kv <= slots) {
+        int lo = 2, hi = 64;
+        while (lo < hi) {  // uniform over the workgroup: every thread sees the same counts
+            const int mid = (lo + hi) / 2;
+            if ((int64_t)count_items(mid) * n_kv <= slots) hi = mid;
+            else lo = mid + 1;
+        }
+        cp = lo;
+    } else {
+        cp = 64;
+        while (cp > 8 && (int64_t)(total / cp) * n_kv < target_waves) cp >>= 1;
     }
-    if (tid == 0) {
-        int total = scan[0];
-        // pages per item: small enough that the list holds several items per wave slot, large enough that
-        // the per-item partial result stays a small fraction of the bytes the item reads, and such that
-        // the list fits (items <= total/cp + batch).
-        int cp = 64;
-        while (cp > 2 && (int64_t)(total / cp) * n_kv < target_waves) cp >>= 1;
-        while (total / cp + batch > cap_items) cp <<= 1;
-        if (force_cp > 0 && total / force_cp + batch <= cap_items) cp = force_cp;
-        s_cp = cp;
-    }
-    __syncthreads();
-    const int cp = s_cp;
+    while (total / cp + batch > cap_items) cp <<= 1;
+    if (force_cp > 0 && total / force_cp + batch <= cap_items) cp = force_cp;
     __syncthreads();
 
     // exclusive scan of items per request
@@ -101,8 +118,9 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
 int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv,
                          hipStream_t st) {
     const Tuning& t = tuning();
-    attn_plan_kernel<<<1, kPlanThreads, 0, st>>>(ws.plan, ws.max_batch, ws.cap_items, seq_lens, len_bias, batch, n_kv,
-                                                  t.attn_target_waves, t.attn_chunk_pages);
+    const int slots = 4 * (t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);  // waves of the persistent attention grid
+    attn_plan_kernel<<<1, kPlanThreads, 0, st>>>(ws.plan, ws.max_batch, ws.cap_items, seq_lens, len_bias, batch, n_kv, slots,
+                                                  t.attn_target_waves > 0 ? t.attn_target_waves : 4 * slots, t.attn_chunk_pages);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }

@@ -48,9 +48,10 @@ struct Tuning {
     int linear_target_blocks = 256; // K is sliced until the grid has about this many workgroups
     int linear_big_min_m = 0;       // rows from which the input is pre-split into tiled bf16 terms (0 = built-in, <0 = never)
     int linear_tile_pad = -1;       // pad between weight tiles in bf16 elements, read when a matrix is packed (-1 = built-in)
+    int linear_ks = 0;              // k-steps of 16 per chunk (depth of the weight ring): 4 or 8
     int linear_big_all = 0;         // 1: pre-split every projection's input from that row count on, not only the SwiGLU one
     int attn_grid = 0;              // workgroups of the persistent attention grid
-    int attn_target_waves = 2048;   // work items aimed for when choosing pages per item
+    int attn_target_waves = 0;      // work items aimed for when one round of the grid cannot hold the list (0 = 4 rounds)
     int attn_chunk_pages = 0;       // forced pages per item
 };
 Tuning& tuning();
