@@ -343,8 +343,9 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     if (prologue != PRO_PACKED && (lda % 4 != 0 || ((uintptr_t)A & 15)))
         return fail(CHIRON_ERR_INVALID_ARG, "linear: input rows must be 16-byte aligned");
     const Tuning& tn = tuning();
-    // Tile shape.  Up to 64 rows the kernel is HBM-bound: 32- or 64-row tiles, two column tiles per wave (one
-    // when that is what it takes to give every CU a workgroup and K cannot be sliced).  From ~384 rows on it is
+    // Tile shape.  Up to 64 rows the kernel is HBM-bound: 32- or 64-row tiles; one column tile per wave when K can
+    // be sliced (twice the workgroups along N, so half the K-slices for the consumer to add up) or when that is
+    // what it takes to give every CU a workgroup, else two.  From ~384 rows on it is
     // matrix-core bound and the 128-row x 4-tile wave shape wins (fewer LDS reads and staging per MFMA), at one
     // wave per SIMD; in between the 64-row shape measured faster.
     const bool big = M >= 384;
@@ -352,7 +353,8 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     int tiles = L.Npad / 32;
     int gz = (M + 32 * mt - 1) / (32 * mt);
     int nf = tn.linear_nf ? tn.linear_nf
-                          : (big && tiles >= 256 ? 4 : ((!part && ((tiles + 7) / 8) * gz < kNumCU) || tiles < 64 ? 1 : 2));
+                          : (big && tiles >= 256 ? 4
+                             : ((!part && ((tiles + 7) / 8) * gz < kNumCU) || tiles < 64 || (part && M <= 64) ? 1 : 2));
     // (MT=2, NF=1, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
     if (prologue == PRO_SWIGLU) nf = 2;
     if (prologue == PRO_PACKED) {  // only the large-batch shapes are built for pre-split input
