@@ -355,13 +355,15 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     int nf = tn.linear_nf ? tn.linear_nf
                           : (big && tiles >= 256 ? 4
                              : ((!part && ((tiles + 7) / 8) * gz < kNumCU) || tiles < 64 || (part && M <= 64) ? 1 : 2));
-    // (MT=2, NF=1, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
+    // (MT=2, NF=1, KS=4, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
+    // (the KS=8 build of it compiles but measured slower than two tiles per wave: 45 vs 36 us at 64 rows)
     if (prologue == PRO_SWIGLU) nf = 2;
     if (prologue == PRO_PACKED) {  // only the large-batch shapes are built for pre-split input
         mt = 4;
         nf = tn.linear_nf ? (tn.linear_nf == 4 ? 4 : 2) : (tiles >= 128 ? 4 : 2);
     }
     if (nf == 4 && mt == 1) mt = 2;
+    gz = (M + 32 * mt - 1) / (32 * mt);  // mt may have changed above
     int gx = (tiles + 4 * nf - 1) / (4 * nf);
     // A projection that cannot slice K (no workspace) runs one workgroup per CU; a ring of 8 k-steps then keeps twice
     // the weight bytes in flight per wave, which measured 9 % faster on the gate/up shape at 64 rows.
