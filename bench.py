@@ -115,6 +115,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=32)
     ap.add_argument("--autoscale-slo-ms", type=float, default=0.0,
                     help="also run the local autoscaler (Alg. 1) closed loop on the measured curve with this ITL SLO")
+    ap.add_argument("--q-len", type=int, default=0, help="also time the multi-token (verify) step with this many new tokens per request")
     ap.add_argument("--swap", action="store_true", help="also time evicting the longest request's cache to pinned host memory and back")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known bytes) so that rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE "
@@ -138,7 +139,8 @@ def main():
     batch = min(a.batch, full_batch) if a.batch > 0 else full_batch
     sample = list(range(min(a.cpu_sample, batch))) if not a.no_cpu_baseline else []
     t0 = time.time()
-    wl = W.build(a.workload, seed=0, host_seqs=sample, host_weights=bool(sample), log=log)
+    wl = W.build(a.workload, seed=0, host_seqs=sample, host_weights=bool(sample), log=log,
+                 max_batch=full_batch * max(1, a.q_len))
     if batch != full_batch:
         wl.context_tokens = int(wl.lens[:batch].astype(np.int64).sum()) + batch
     log("workload %s built in %.1f s: batch %d, %d context tokens, pool %d pages" % (
@@ -228,6 +230,31 @@ def main():
             tput_prev = pt["tokens_per_s"] if new > mbs else 0.0   # after a scale-down there is nothing comparable
             mbs = new
         out["autoscale"] = dict(itl_slo_ms=a.autoscale_slo_ms, alpha=0.5, trajectory=traj)
+
+    if a.q_len > 1:
+        # verify step of speculative decoding: q_len new tokens per request in one pass (the last q_len-1 cached
+        # tokens are treated as not yet cached so that the new positions lie in allocated pages)
+        T = a.q_len
+        if batch * T > wl.model.cfg.max_batch:
+            log("--q-len %d skipped: batch*q_len exceeds the model's max_batch" % T)
+        else:
+            lens_m = torch.from_numpy((wl.lens[:batch] - (T - 1)).clip(min=0).astype(np.int32)).cuda()
+            from paper_2501_08090_amd import inputs as I
+            toks_m = torch.from_numpy(I.token_ids(batch * T, wl.m["vocab"], 9).reshape(batch, T)).cuda()
+            lg_m = torch.empty((batch, T, wl.m["vocab"]), dtype=torch.float32, device="cuda")
+            bt_m = wl.block_table[:batch].contiguous()
+            for _ in range(2):
+                B.decode_step_multi(wl.model, wl.pool, bt_m, lens_m, toks_m, logits=lg_m)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(a.steps):
+                B.decode_step_multi(wl.model, wl.pool, bt_m, lens_m, toks_m, logits=lg_m)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / a.steps
+            out["multi_token"] = dict(q_len=T, ms_per_step=round(dt * 1e3, 4), rows_per_s=round(batch * T / dt, 1),
+                                      vs_single_token_step=round(dt * 1e3 / out["ms_per_step"], 3))
+            log("multi-token step (q_len %d): %.3f ms = %.2fx the single-token step, %.0f rows/s" % (
+                T, dt * 1e3, dt * 1e3 / out["ms_per_step"], batch * T / dt))
 
     if a.swap:
         # eviction path: the longest request's pages to pinned host memory and back (kernels write/read the host

@@ -17,12 +17,13 @@ def pages_needed(lens, bs=16):
     return (np.asarray(lens, np.int64) + 1 + bs - 1) // bs
 
 
-def run(m, w_host, kv_host, lens, tokens):
-    """lens/tokens: the sampled requests' context lengths and input tokens; kv_host[l] = (K, V) rows of those
-    requests, sequence-major.  Returns (logits, pool, block_table, seconds_of_the_step)."""
+def run(m, w_host, kv_host, lens, tokens, q_len=1):
+    """lens/tokens: the sampled requests' context lengths and input tokens (tokens [n] or, with q_len > 1,
+    [n, q_len]); kv_host[l] = (K, V) rows of those requests, sequence-major.
+    Returns (logits, pool, block_table, seconds_of_the_step)."""
     cfg = orc.make_config(m, orc.BF16, orc.BF16)
     lens = np.asarray(lens, np.int32)
-    need = pages_needed(lens)
+    need = pages_needed(lens + (q_len - 1))
     bt = np.full((len(lens), int(need.max())), -1, np.int32)
     o = 0
     for r, c in enumerate(need):
@@ -37,5 +38,8 @@ def run(m, w_host, kv_host, lens, tokens):
         vf = (v.astype(np.uint32) << 16).view(np.float32)
         orc.append_kv(pool, l, kf, vf, bt, seq_idx, pos)
     t0 = time.perf_counter()
-    logits, _ = orc.decode_step(cfg, w_host, pool, bt, lens, np.asarray(tokens, np.int32))
+    if q_len > 1:
+        logits = orc.decode_step_multi(cfg, w_host, pool, bt, lens, np.asarray(tokens, np.int32).reshape(len(lens), q_len))
+    else:
+        logits, _ = orc.decode_step(cfg, w_host, pool, bt, lens, np.asarray(tokens, np.int32))
     return logits, pool, bt, time.perf_counter() - t0

@@ -31,7 +31,7 @@ constexpr int kPlanThreads = 1024;
 
 __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __restrict__ plan, int max_batch, int cap_items,
                                                                  const int32_t* __restrict__ seq_lens, int len_bias,
-                                                                 int batch, int n_kv, int slots, int target_waves, int force_cp) {
+                                                                 int batch, int n_kv, int slots, int target_waves, int force_cp, int item_limit) {
     __shared__ int scan[kPlanThreads];
     int32_t* seq_item0 = plan + 4;
     int32_t* seq_nch = plan + 4 + max_batch;
@@ -79,8 +79,8 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
         cp = 64;
         while (cp > 8 && (int64_t)(total / cp) * n_kv < target_waves) cp >>= 1;
     }
-    while (total / cp + batch > cap_items) cp <<= 1;
-    if (force_cp > 0 && total / force_cp + batch <= cap_items) cp = force_cp;
+    while (total / cp + batch > item_limit) cp <<= 1;
+    if (force_cp > 0 && total / force_cp + batch <= item_limit) cp = force_cp;
     __syncthreads();
 
     // exclusive scan of items per request
@@ -115,19 +115,23 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     }
 }
 
-int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv,
+int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv, int q_len,
                          hipStream_t st) {
     const Tuning& t = tuning();
     const int slots = 4 * (t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);  // waves of the persistent attention grid
     attn_plan_kernel<<<1, kPlanThreads, 0, st>>>(ws.plan, ws.max_batch, ws.cap_items, seq_lens, len_bias, batch, n_kv, slots,
-                                                  t.attn_target_waves > 0 ? t.attn_target_waves : 4 * slots, t.attn_chunk_pages);
+                                                  t.attn_target_waves > 0 ? t.attn_target_waves : 4 * slots, t.attn_chunk_pages,
+                                                  ws.cap_items / q_len);  // a partial result holds q_len tokens' heads
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
 
 // ---- the attention kernel ---------------------------------------------------------------------------
-template <int D, int G>
-__global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, const float* __restrict__ q, int ldq,
+// MULTI: every request brings T = q_len new tokens (rows i*T .. i*T+T-1 of q), all already appended; operand column
+// t*G + g is query head g of token t, which sees positions < len - (T-1) + t.  One pass over the request's pages
+// serves all T tokens (G*T <= 16 columns).
+template <int D, int G, bool MULTI>
+__global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, const float* __restrict__ q, int ldq, int T,
                                                          const int32_t* __restrict__ bt, int max_blocks,
                                                          const int32_t* __restrict__ seq_lens, int len_bias,
                                                          const int32_t* __restrict__ plan, int max_batch, int cap_items,
@@ -144,6 +148,8 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
     const int32_t* item_seq = plan + 4 + 2 * max_batch;
     const int32_t* item_pg0 = item_seq + cap_items;
     const int head = lane & 15, lg = lane >> 4;
+    const int cols = MULTI ? G * T : G;              // live operand columns
+    const int tq = MULTI ? head / G : 0, hq = MULTI ? head % G : head;
     const size_t tile_elems = (size_t)16 * D;
 
     // item metadata (request, first page, length) is fetched one item ahead
@@ -204,9 +210,10 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                 }
                 if (TAIL) {
                     const int len_eff = (pg + u < pg1) ? len : 0;
+                    const int len_col = MULTI ? min(len_eff, len - (T - 1) + tq) : len_eff;  // causal among the new tokens
                     const int tok0 = (pg + u) * 16 + lg * 4;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) s[u][r] = (tok0 + r < len_eff) ? s[u][r] : -INFINITY;
+                    for (int r = 0; r < 4; ++r) s[u][r] = (tok0 + r < len_col) ? s[u][r] : -INFINITY;
                     // slots past the end may hold any bits (NaN included): clear their V so that 0 * V stays 0
                     int valid = len_eff - tok0;
                     uint32_t m01 = (valid > 0 ? 0x0000ffffu : 0u) | (valid > 1 ? 0xffff0000u : 0u);
@@ -222,7 +229,9 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            // a column can have nothing visible yet (an item that starts among the new tokens): keep the exponents finite
+            const float m_use = MULTI ? fmaxf(m_new, -1e30f) : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
             m_run = m_new;
             l_run *= alpha;
 #pragma unroll
@@ -232,7 +241,7 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                 float pr[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    pr[r] = __builtin_amdgcn_exp2f(s[u][r] - m_new);
+                    pr[r] = __builtin_amdgcn_exp2f(s[u][r] - m_use);
                     l_run += pr[r];
                 }
                 uint2 ph, pl;
@@ -268,8 +277,8 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
         // q fragments: operand column = head, 8 consecutive dims per lane group; scaled by log2(e)/sqrt(d)
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
-            if (head < G) {
-                const float* qp = q + (size_t)i * ldq + (size_t)(c * G + head) * D + s * 32 + lg * 8;
+            if (head < cols) {
+                const float* qp = q + (size_t)(MULTI ? i * T + tq : i) * ldq + (size_t)(c * G + hq) * D + s * 32 + lg * 8;
                 float4 a = *reinterpret_cast<const float4*>(qp), b = *reinterpret_cast<const float4*>(qp + 4);
                 split2(a.x * scale_log2e, a.y * scale_log2e, qh[s].x, ql[s].x);
                 split2(a.z * scale_log2e, a.w * scale_log2e, qh[s].y, ql[s].y);
@@ -284,7 +293,7 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
             load_group(kn, vn);
             fetch_ids(pg + 2 * NPG);
             __builtin_amdgcn_sched_barrier(0);
-            compute(pg, std::false_type{});
+            compute(pg, std::integral_constant<bool, MULTI>{});  // the new tokens' masks can reach into the stage before the last
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < NPG; ++u)
@@ -299,10 +308,10 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
         // each lane group summed its own tokens; combine the four groups
         l_run += __shfl_xor(l_run, 16);
         l_run += __shfl_xor(l_run, 32);
-        if (head < G) {
-            const size_t slot = (size_t)w * G + head;
+        if (head < cols) {
+            const size_t slot = (size_t)w * cols + head;
             if (lg == 0) {
-                part_ml[slot * 2] = m_run;
+                part_ml[slot * 2] = MULTI ? fmaxf(m_run, -1e30f) : m_run;
                 part_ml[slot * 2 + 1] = l_run;
             }
 #pragma unroll
@@ -316,14 +325,15 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
 // 256 threads = 8 item slices x 32 lanes of float4 (D = 128) or 16 slices x 16 lanes (D = 64); slice k takes
 // items k, k+S, ...; the slices are combined through LDS in a fixed order.
 template <int D>
-__global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restrict__ plan, int max_batch, int n_kv, int G,
+__global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restrict__ plan, int max_batch, int n_kv, int G, int T,
                                                           const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml, float* __restrict__ out,
                                                           int ldo) {
     constexpr int LANES = D / 4, S = 256 / LANES;
     __shared__ float4 s_num[S][LANES];
     __shared__ float s_den[S], s_max[S];
-    const int i = blockIdx.x, a = blockIdx.y, c = a / G, j = a % G;
+    // row = request * T + token; a partial result holds G*T columns per (item, kv head), column = token*G + head
+    const int row = blockIdx.x, i = row / T, tq = row % T, a = blockIdx.y, c = a / G, j = tq * G + a % G, GT = G * T;
     const int sl = threadIdx.x / LANES, ln = threadIdx.x % LANES;
     const int item0 = plan[4 + i], nch = plan[4 + max_batch + i];
     // each slice folds its items with a running maximum, two items' loads in flight at a time
@@ -339,7 +349,7 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restr
     };
     int ch = sl;
     for (; ch + S < nch; ch += 2 * S) {
-        size_t s0 = ((size_t)(item0 + ch) * n_kv + c) * G + j, s1 = ((size_t)(item0 + ch + S) * n_kv + c) * G + j;
+        size_t s0 = ((size_t)(item0 + ch) * n_kv + c) * GT + j, s1 = ((size_t)(item0 + ch + S) * n_kv + c) * GT + j;
         float2 ml0 = *reinterpret_cast<const float2*>(part_ml + s0 * 2), ml1 = *reinterpret_cast<const float2*>(part_ml + s1 * 2);
         float4 o0 = *reinterpret_cast<const float4*>(part_o + s0 * D + ln * 4);
         float4 o1 = *reinterpret_cast<const float4*>(part_o + s1 * D + ln * 4);
@@ -347,7 +357,7 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restr
         fold(ml1.x, ml1.y, o1);
     }
     if (ch < nch) {
-        size_t s0 = ((size_t)(item0 + ch) * n_kv + c) * G + j;
+        size_t s0 = ((size_t)(item0 + ch) * n_kv + c) * GT + j;
         float2 ml0 = *reinterpret_cast<const float2*>(part_ml + s0 * 2);
         fold(ml0.x, ml0.y, *reinterpret_cast<const float4*>(part_o + s0 * D + ln * 4));
     }
@@ -369,18 +379,26 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restr
             n4.x += wk * t.x; n4.y += wk * t.y; n4.z += wk * t.z; n4.w += wk * t.w;
         }
         float inv = 1.0f / dsum;
-        *reinterpret_cast<float4*>(out + (size_t)i * ldo + (size_t)a * D + ln * 4) =
+        *reinterpret_cast<float4*>(out + (size_t)row * ldo + (size_t)a * D + ln * 4) =
             make_float4(n4.x * inv, n4.y * inv, n4.z * inv, n4.w * inv);
     }
 }
 
 template <int D>
-static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p, int layer, const float* q, int ldq,
+static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p, int layer, const float* q, int ldq, int T,
                              const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias,
                              const AttnWorkspace& ws, float scale) {
 #define CHIRON_ATTN(G_)                                                                                              \
-    paged_attn_kernel<D, G_><<<grid, 256, 0, st>>>(p, layer, q, ldq, bt, max_blocks, seq_lens, len_bias, ws.plan,     \
-                                                   ws.max_batch, ws.cap_items, ws.part_o, ws.part_ml, scale)
+    do {                                                                                                             \
+        if (T > 1)                                                                                                   \
+            paged_attn_kernel<D, G_, true><<<grid, 256, 0, st>>>(p, layer, q, ldq, T, bt, max_blocks, seq_lens,      \
+                                                                 len_bias, ws.plan, ws.max_batch, ws.cap_items,      \
+                                                                 ws.part_o, ws.part_ml, scale);                      \
+        else                                                                                                         \
+            paged_attn_kernel<D, G_, false><<<grid, 256, 0, st>>>(p, layer, q, ldq, 1, bt, max_blocks, seq_lens,     \
+                                                                  len_bias, ws.plan, ws.max_batch, ws.cap_items,     \
+                                                                  ws.part_o, ws.part_ml, scale);                     \
+    } while (0)
     switch (G) {
         case 1: CHIRON_ATTN(1); break;
         case 2: CHIRON_ATTN(2); break;
@@ -394,29 +412,30 @@ static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p
 }
 
 int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
-                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch,
+                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch, int q_len,
                          hipStream_t st) {
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
+    if (q_len < 1 || G * q_len > 16) return fail(CHIRON_ERR_INVALID_ARG, "attention: %d tokens x %d heads per KV head exceed 16 operand columns", q_len, G);
     const float scale = (float)(1.4426950408889634 / std::sqrt((double)p.d));
     const Tuning& t = tuning();
     dim3 grid(t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);
     int32_t rc;
-    if (p.d == 128) rc = launch_attn_d<128>(G, grid, st, p, layer, q, ldq, bt, max_blocks, seq_lens, len_bias, ws, scale);
-    else if (p.d == 64) rc = launch_attn_d<64>(G, grid, st, p, layer, q, ldq, bt, max_blocks, seq_lens, len_bias, ws, scale);
+    if (p.d == 128) rc = launch_attn_d<128>(G, grid, st, p, layer, q, ldq, q_len, bt, max_blocks, seq_lens, len_bias, ws, scale);
+    else if (p.d == 64) rc = launch_attn_d<64>(G, grid, st, p, layer, q, ldq, q_len, bt, max_blocks, seq_lens, len_bias, ws, scale);
     else return fail(CHIRON_ERR_SHAPE, "attention: head_dim must be 64 or 128 (got %d)", p.d);
     if (rc) return rc;
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
 
-int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, int batch, float* out, int ldo,
+int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, int batch, int q_len, float* out, int ldo,
                           hipStream_t st) {
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
-    dim3 rgrid(batch, n_q);
-    if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
-    else attn_reduce_kernel<64><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, ws.part_o, ws.part_ml, out, ldo);
+    dim3 rgrid(batch * q_len, n_q);
+    if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, q_len, ws.part_o, ws.part_ml, out, ldo);
+    else attn_reduce_kernel<64><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, q_len, ws.part_o, ws.part_ml, out, ldo);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }

@@ -117,12 +117,14 @@ struct AttnWorkspace {
 };
 int64_t attn_plan_ints(int max_batch, int cap_items);
 // builds the work list for attend lengths len_i = seq_lens[i] + len_bias
-int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv,
+// q_len > 1: each request brings q_len new tokens (already appended; len_bias = q_len) that share one pass over its
+// pages: q and out hold rows request*q_len + token, token t sees positions <= seq_lens[i] + t.  n_q/n_kv * q_len <= 16.
+int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv, int q_len,
                          hipStream_t st);
 int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
-                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch,
+                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch, int q_len,
                          hipStream_t st);
-int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, int batch, float* out, int ldo,
+int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, int batch, int q_len, float* out, int ldo,
                           hipStream_t st);
 
 }  // namespace chiron

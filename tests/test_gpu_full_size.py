@@ -89,6 +89,39 @@ def test_8b_batch64_lognormal(model8b):
     check_workload("llama8b-b64-lognormal800", model8b, sample, batches=(1, 8, 33))
 
 
+def test_8b_batch64_multi_token_step(model8b):
+    """The verify shape of speculative decoding at full size: 64 requests x 4 new tokens (256 rows; 4 tokens x 4 query
+    heads per KV head fill the 16 operand columns of the attention kernel, so a request's pages are read once).
+    The last three cached tokens of every request are treated as not yet cached, so that the four new positions
+    lie in pages the workload has allocated."""
+    B, W = _mods()
+    model, w_host = model8b
+    T = 4
+    sample = [0, 31, 63]
+    wl = W.build("llama8b-b64-lognormal800", seed=0, host_seqs=sample, model=model, w_host=w_host)
+    lens = (wl.lens - (T - 1)).astype(np.int32)
+    toks = I.token_ids(wl.batch * T, wl.m["vocab"], 9).reshape(wl.batch, T)
+    logits = B.decode_step_multi(wl.model, wl.pool, wl.block_table, torch.from_numpy(lens).cuda(), torch.from_numpy(toks).cuda())
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(logits).all())
+    got = logits[sample].cpu().numpy().reshape(len(sample) * T, -1)
+    starts = np.concatenate([[0], np.cumsum(wl.lens[sample].astype(np.int64))])
+    keep = np.concatenate([np.arange(starts[r], starts[r] + lens[i]) for r, i in enumerate(sample)])
+    kv = [(k[keep], v[keep]) for k, v in wl.kv_host]
+    want, _, _, dt = sample_step.run(wl.m, wl.w_host, kv, lens[sample], toks[sample], q_len=T)
+    want = want.reshape(len(sample) * T, -1)
+    err = np.abs(got - want).max() / want.std()
+    agree = (got.argmax(1) == want.argmax(1)).mean()
+    print("multi-token: sampled rows max|d|/sigma = %.3e, argmax agreement %.3f, oracle %.1f s" % (err, agree, dt), flush=True)
+    assert err <= STEP_TOL and agree >= 0.99
+    # token 0 of every request is what a single-token step computes at the same state (pool rewritten identically)
+    one = B.decode_step(wl.model, wl.pool, wl.block_table, torch.from_numpy(lens).cuda(),
+                        torch.from_numpy(np.ascontiguousarray(toks[:, 0])).cuda())
+    d = (one - logits[:, 0]).abs().max().item() / want.std()
+    print("token 0 vs single-token step: max|d|/sigma = %.2e" % d, flush=True)
+    assert d <= 1e-2
+
+
 def test_8b_batch512_mixed_population(model8b):
     lens = I.population("mixed", 512, 0)
     sample = sorted({0, 3, int(lens.argmin()), 255, 511})

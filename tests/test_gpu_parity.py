@@ -320,11 +320,18 @@ def test_decode_step_medium_shape_d128():
     check_logits(got, want, min_agree=0.99)
 
 
-@pytest.mark.parametrize("T", [2, 4])
-def test_multi_token_step(T):
-    """q_len > 1 (speculative-decoding verify shape): causal over the block, all T tokens' K/V appended."""
-    lens = [14, 31, 60, 0, 127]
-    c = make_case(seed=16, storage="bf16", gain_jitter=0.1, seq_lens=lens, pool_factor=3.0)
+G4_D128 = dict(I.TINY, head_dim=128, n_kv_heads=2, n_q_heads=8)
+
+
+@pytest.mark.parametrize("m,T", [(I.TINY, 2), (I.TINY, 4), (I.TINY, 8), (I.TINY, 9), (G4_D128, 4), (G4_D128, 3), (G4_D128, 5)])
+def test_multi_token_step(m, T):
+    """q_len > 1 (speculative-decoding verify shape): causal over the block, all T tokens' K/V appended.
+    While heads-per-KV-head x T <= 16 the T tokens share one pass over the request's pages (operand columns
+    token*G + head); beyond that every row attends on its own.  Lengths 15, 31, 63 put the first new token at
+    the end of a page / of a work item, so that later tokens open a page or an item in which the earlier ones
+    see nothing."""
+    lens = [14, 15, 31, 63, 60, 0, 127, 1]
+    c = make_case(m=m, seed=16, storage="bf16", gain_jitter=0.1, seq_lens=lens, pool_factor=3.0)
     toks = I.token_ids(len(lens) * T, c.m["vocab"], 6).reshape(len(lens), T)
     bt, nb = I.make_block_table(np.asarray(lens) + T - 1, seed=16, pool_factor=3.0)
     c.block_table, c.num_blocks = bt, nb
