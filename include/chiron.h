@@ -179,6 +179,15 @@ int32_t chiron_check_step_inputs_host(const chiron_model_config *cfg, int32_t nu
                                       const int32_t *block_table, const int32_t *seq_lens, const int32_t *tokens,
                                       int32_t batch);
 
+/* The two checks above for the inputs of chiron_decode_step_multi: tokens holds [batch, q_len] ids, every page that
+ * holds one of the positions seq_lens[i] .. seq_lens[i]+q_len-1 counts as written, batch*q_len <= max_batch. */
+int32_t chiron_validate_step_inputs_multi(const chiron_model *m, const chiron_kvpool *p, const int32_t *block_table,
+                                          const int32_t *seq_lens, const int32_t *tokens, int32_t batch, int32_t q_len,
+                                          void *stream);
+int32_t chiron_check_step_inputs_host_multi(const chiron_model_config *cfg, int32_t num_blocks, int32_t block_size,
+                                            const int32_t *block_table, const int32_t *seq_lens, const int32_t *tokens,
+                                            int32_t batch, int32_t q_len);
+
 /* One point of the curve the local autoscaler walks (Local Autoscaler: LBP is observed
  * ITL over the ITL SLO, TBP is previous over current throughput). */
 typedef struct {

@@ -21,7 +21,8 @@ SYMBOLS = [
     "chiron_model_create", "chiron_model_load_layer", "chiron_model_load_head", "chiron_model_destroy",
     "chiron_kv_block_bytes", "chiron_kv_pool_create", "chiron_kv_pool_destroy", "chiron_append_kv", "chiron_gather_kv",
     "chiron_kv_swap_out", "chiron_kv_swap_in",
-    "chiron_decode_step", "chiron_decode_step_multi", "chiron_validate_step_inputs", "chiron_check_step_inputs_host", "chiron_step_latency_profile",
+    "chiron_decode_step", "chiron_decode_step_multi", "chiron_validate_step_inputs", "chiron_check_step_inputs_host",
+    "chiron_validate_step_inputs_multi", "chiron_check_step_inputs_host_multi", "chiron_step_latency_profile",
     "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end", "chiron_local_autoscale_step",
     "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_op_swiglu_linear",
     "chiron_op_rope", "chiron_op_paged_attention", "chiron_set_tuning",
@@ -200,18 +201,26 @@ def decode_step_multi(model, pool, block_table, seq_lens, tokens, logits=None):
 
 
 def validate_step_inputs(model, pool, block_table, seq_lens, tokens, batch=None):
+    """tokens [batch] or, for the multi-token step, [batch, q_len]"""
     B = seq_lens.numel() if batch is None else int(batch)
+    if tokens.dim() == 2:
+        _check(load().chiron_validate_step_inputs_multi(model._h, pool._h, _ptr(block_table, torch.int32), _ptr(seq_lens, torch.int32),
+                                                        _ptr(tokens, torch.int32), C.c_int32(B), C.c_int32(tokens.shape[1]), _stream()))
+        return
     _check(load().chiron_validate_step_inputs(model._h, pool._h, _ptr(block_table, torch.int32), _ptr(seq_lens, torch.int32),
                                               _ptr(tokens, torch.int32), C.c_int32(B), _stream()))
 
 
 def check_step_inputs_host(cfg, num_blocks, block_table, seq_lens, tokens, block_size=16):
-    """Host-only check of index arrays (numpy int32)."""
+    """Host-only check of index arrays (numpy int32); tokens [batch] or [batch, q_len]."""
     import numpy as np
     bt = np.ascontiguousarray(block_table, np.int32)
     sl = np.ascontiguousarray(seq_lens, np.int32)
     tk = np.ascontiguousarray(tokens, np.int32)
     p = lambda a: a.ctypes.data_as(C.c_void_p)
+    if tk.ndim == 2:
+        return int(load().chiron_check_step_inputs_host_multi(C.byref(cfg), C.c_int32(num_blocks), C.c_int32(block_size), p(bt),
+                                                              p(sl), p(tk), C.c_int32(sl.size), C.c_int32(tk.shape[1])))
     return int(load().chiron_check_step_inputs_host(C.byref(cfg), C.c_int32(num_blocks), C.c_int32(block_size), p(bt), p(sl),
                                                     p(tk), C.c_int32(sl.size)))
 

@@ -380,20 +380,25 @@ int32_t chiron_decode_step_multi(chiron_model* m, chiron_kvpool* p, const int32_
     return step_rows(m, p, m->x_bt, m->x_lens, tokens, batch * q_len, m->x_bt, m->x_lens, 1, logits, (hipStream_t)stream);
 }
 
-int32_t chiron_check_step_inputs_host(const chiron_model_config* cfg, int32_t num_blocks, int32_t block_size,
-                                      const int32_t* block_table, const int32_t* seq_lens, const int32_t* tokens,
-                                      int32_t batch) {
+static int32_t check_inputs_host(const chiron_model_config* cfg, int32_t num_blocks, int32_t block_size,
+                                 const int32_t* block_table, const int32_t* seq_lens, const int32_t* tokens, int32_t batch,
+                                 int32_t q_len) {
     if (!cfg) return fail(CHIRON_ERR_INVALID_ARG, "config is null");
     if (batch < 0) return fail(CHIRON_ERR_INVALID_ARG, "batch is negative");
-    if (batch > cfg->max_batch) return fail(CHIRON_ERR_BATCH_TOO_LARGE, "batch %d exceeds max_batch %d", batch, cfg->max_batch);
+    if (q_len < 1) return fail(CHIRON_ERR_INVALID_ARG, "q_len must be at least 1");
+    if ((int64_t)batch * q_len > cfg->max_batch)
+        return fail(CHIRON_ERR_BATCH_TOO_LARGE, "batch*q_len = %lld exceeds max_batch %d", (long long)batch * q_len, cfg->max_batch);
     if (block_size != kBlockSize) return fail(CHIRON_ERR_INVALID_ARG, "block_size %d: must be 16", block_size);
     if (batch > 0 && (!block_table || !seq_lens || !tokens)) return fail(CHIRON_ERR_INVALID_ARG, "an index array is null");
     std::unordered_set<int32_t> written;
     for (int i = 0; i < batch; ++i) {
-        if (tokens[i] < 0 || tokens[i] >= cfg->vocab)
-            return fail(CHIRON_ERR_TOKEN, "tokens[%d] = %d is outside [0, %d)", i, tokens[i], cfg->vocab);
+        for (int t = 0; t < q_len; ++t) {
+            const int32_t tok = tokens[(size_t)i * q_len + t];
+            if (tok < 0 || tok >= cfg->vocab)
+                return fail(CHIRON_ERR_TOKEN, "tokens[%d] = %d is outside [0, %d)", i * q_len + t, tok, cfg->vocab);
+        }
         if (seq_lens[i] < 0) return fail(CHIRON_ERR_INVALID_ARG, "seq_lens[%d] = %d is negative", i, seq_lens[i]);
-        int64_t need = ((int64_t)seq_lens[i] + 1 + block_size - 1) / block_size;
+        int64_t need = ((int64_t)seq_lens[i] + q_len + block_size - 1) / block_size;
         if (need > cfg->max_blocks_per_seq)
             return fail(CHIRON_ERR_BLOCK_TABLE, "request %d needs %lld pages, block table rows hold %d", i, (long long)need,
                         cfg->max_blocks_per_seq);
@@ -402,9 +407,10 @@ int32_t chiron_check_step_inputs_host(const chiron_model_config* cfg, int32_t nu
             if (row[b] < 0 || row[b] >= num_blocks)
                 return fail(CHIRON_ERR_BLOCK_TABLE, "block_table[%d][%lld] = %d is not a page of the pool (%d pages)", i,
                             (long long)b, row[b], num_blocks);
-        int32_t wpage = row[seq_lens[i] / block_size];
-        if (!written.insert(wpage).second)
-            return fail(CHIRON_ERR_BLOCK_TABLE, "page %d is written by more than one request (request %d)", wpage, i);
+        // the pages that hold positions seq_lens[i] .. seq_lens[i]+q_len-1 are written
+        for (int64_t b = seq_lens[i] / block_size; b < need; ++b)
+            if (!written.insert(row[b]).second)
+                return fail(CHIRON_ERR_BLOCK_TABLE, "page %d is written by more than one request (request %d)", row[b], i);
     }
     // a page that one request writes must not be read by another (shared pages are read-only)
     for (int i = 0; i < batch; ++i) {
@@ -417,19 +423,43 @@ int32_t chiron_check_step_inputs_host(const chiron_model_config* cfg, int32_t nu
     return CHIRON_OK;
 }
 
-int32_t chiron_validate_step_inputs(const chiron_model* m, const chiron_kvpool* p, const int32_t* block_table,
-                                    const int32_t* seq_lens, const int32_t* tokens, int32_t batch, void* stream) {
+int32_t chiron_check_step_inputs_host(const chiron_model_config* cfg, int32_t num_blocks, int32_t block_size,
+                                      const int32_t* block_table, const int32_t* seq_lens, const int32_t* tokens,
+                                      int32_t batch) {
+    return check_inputs_host(cfg, num_blocks, block_size, block_table, seq_lens, tokens, batch, 1);
+}
+
+int32_t chiron_check_step_inputs_host_multi(const chiron_model_config* cfg, int32_t num_blocks, int32_t block_size,
+                                            const int32_t* block_table, const int32_t* seq_lens, const int32_t* tokens,
+                                            int32_t batch, int32_t q_len) {
+    return check_inputs_host(cfg, num_blocks, block_size, block_table, seq_lens, tokens, batch, q_len);
+}
+
+static int32_t validate_on_device(const chiron_model* m, const chiron_kvpool* p, const int32_t* block_table,
+                                  const int32_t* seq_lens, const int32_t* tokens, int32_t batch, int32_t q_len, void* stream) {
+    if (q_len < 1) return fail(CHIRON_ERR_INVALID_ARG, "q_len must be at least 1");
     int32_t rc = check_step_args(m, p, block_table, seq_lens, tokens, batch);
     if (rc) return rc;
     if (batch == 0) return CHIRON_OK;
     hipStream_t st = (hipStream_t)stream;
     const int mb = m->cfg.max_blocks_per_seq;
-    std::vector<int32_t> bt((size_t)batch * mb), sl(batch), tk(batch);
+    std::vector<int32_t> bt((size_t)batch * mb), sl(batch), tk((size_t)batch * q_len);
     CHIRON_HIP(hipMemcpyAsync(bt.data(), block_table, bt.size() * 4, hipMemcpyDeviceToHost, st));
     CHIRON_HIP(hipMemcpyAsync(sl.data(), seq_lens, sl.size() * 4, hipMemcpyDeviceToHost, st));
     CHIRON_HIP(hipMemcpyAsync(tk.data(), tokens, tk.size() * 4, hipMemcpyDeviceToHost, st));
     CHIRON_HIP(hipStreamSynchronize(st));
-    return chiron_check_step_inputs_host(&m->cfg, p->d.num_blocks, p->block_size, bt.data(), sl.data(), tk.data(), batch);
+    return check_inputs_host(&m->cfg, p->d.num_blocks, p->block_size, bt.data(), sl.data(), tk.data(), batch, q_len);
+}
+
+int32_t chiron_validate_step_inputs(const chiron_model* m, const chiron_kvpool* p, const int32_t* block_table,
+                                    const int32_t* seq_lens, const int32_t* tokens, int32_t batch, void* stream) {
+    return validate_on_device(m, p, block_table, seq_lens, tokens, batch, 1, stream);
+}
+
+int32_t chiron_validate_step_inputs_multi(const chiron_model* m, const chiron_kvpool* p, const int32_t* block_table,
+                                          const int32_t* seq_lens, const int32_t* tokens, int32_t batch, int32_t q_len,
+                                          void* stream) {
+    return validate_on_device(m, p, block_table, seq_lens, tokens, batch, q_len, stream);
 }
 
 int32_t chiron_step_latency_profile(chiron_model* m, chiron_kvpool* p, const int32_t* block_table,

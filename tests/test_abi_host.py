@@ -91,3 +91,23 @@ def test_host_validation_of_index_arrays():
     assert chk(lens=np.array([5, -1, 40], np.int32)) == -1
     big = np.zeros(5, np.int32)
     assert B.check_step_inputs_host(cfg, 6, np.zeros((5, 4), np.int32), big, big) == -3
+
+
+def test_host_validation_of_multi_token_inputs():
+    """positions L .. L+q_len-1 are written: their pages must exist and belong to one request only"""
+    cfg = B.make_config(I.TINY, 12, 4)
+    lens = np.array([5, 14, 40], np.int32)
+    bt = np.array([[3, -1, -1, -1], [0, 1, -1, -1], [2, 4, 5, -1]], np.int32)
+    tok = np.arange(9, dtype=np.int32).reshape(3, 3)
+    chk = lambda **k: B.check_step_inputs_host(cfg, k.get("nb", 6), k.get("bt", bt), k.get("lens", lens), k.get("tok", tok))
+    assert chk() == 0                                             # request 1 writes positions 14, 15, 16: pages 0 and 1
+    b2 = bt.copy(); b2[1, 1] = -1
+    assert chk(bt=b2) == -4                                       # ... so its second page must exist
+    assert B.check_step_inputs_host(cfg, 6, b2, lens, tok[:, :2]) == 0   # two tokens stay in the first page
+    b3 = bt.copy(); b3[0, 0] = 1
+    assert chk(bt=b3) == -4 and "more than one" in B.last_error() # page 1 is written by requests 0 and 1
+    t2 = tok.copy(); t2[2, 2] = 5000
+    assert chk(tok=t2) == -7 and "tokens[8]" in B.last_error()
+    assert chk(lens=np.array([5, 14, 62], np.int32)) == -4        # 62 + 3 positions need 5 pages, rows hold 4
+    assert B.check_step_inputs_host(cfg, 6, np.zeros((5, 4), np.int32), np.zeros(5, np.int32), np.zeros((5, 3), np.int32)) == -3
+

@@ -336,6 +336,7 @@ def test_multi_token_step(m, T):
     bt, nb = I.make_block_table(np.asarray(lens) + T - 1, seed=16, pool_factor=3.0)
     c.block_table, c.num_blocks = bt, nb
     g = gpu_setup(c, max_batch=len(lens) * T, poison=True)
+    B().validate_step_inputs(g.model, g.pool, g.block_table, g.seq_lens, torch.from_numpy(toks).cuda())
     got = B().decode_step_multi(g.model, g.pool, g.block_table, g.seq_lens, torch.from_numpy(toks).cuda()).cpu().numpy()
     opool = fresh_pool(c)
     want = orc.decode_step_multi(c.cfg, c.w, opool, bt, c.seq_lens, toks)
