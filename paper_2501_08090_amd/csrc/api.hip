@@ -24,7 +24,7 @@ int32_t fail(int32_t code, const char* fmt, ...) {
 }
 
 // smallest max_batch for which the model carries the workspace of the large-batch projection kernel
-static constexpr int kBigWorkspaceMinBatch = 128;
+static constexpr int kBigWorkspaceMinBatch = 96;
 // bf16 elements between consecutive 32-row weight tiles beyond 32*Kpad (see Linear::tstride)
 static constexpr int kTilePad = 0;
 
@@ -555,7 +555,7 @@ static int32_t op_linear_common(const Linear& L, const float* x, int lda, int M,
     const bool may_split = L.N <= 16384;
     if (may_split) CHIRON_HIP(hipMallocAsync((void**)&part, (size_t)msplit * M * L.N * sizeof(float), st));
     uint16_t* asplit = nullptr;
-    if (M >= linear_big_min_rows()) CHIRON_HIP(hipMallocAsync((void**)&asplit, 2 * linear_big_split_elems(M, L.Kpad) * 2, st));
+    if (M >= linear_big_min_rows(L)) CHIRON_HIP(hipMallocAsync((void**)&asplit, 2 * linear_big_split_elems(M, L.Kpad) * 2, st));
     int ks = 1;
     int32_t rc = launch_linear(L, x, lda, M, y, L.N, accumulate, prologue, part, msplit, &ks, asplit, st);
     if (asplit) (void)hipFreeAsync(asplit, st);

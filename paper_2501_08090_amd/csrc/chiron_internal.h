@@ -67,7 +67,7 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
 int32_t launch_linear_big(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
                           float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st);
 size_t linear_big_split_elems(int M, int Kpad);
-int linear_big_min_rows();
+int linear_big_min_rows(const Linear& L);
 int linear_max_split();
 int32_t launch_reduce_partials(const float* part, int ks, int64_t n, float* y, int accumulate, hipStream_t st);
 int32_t launch_pack_rows(const uint16_t* src, int rows, int K, size_t tstride, uint16_t* dst_packed, int row_offset,

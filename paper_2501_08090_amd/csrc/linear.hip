@@ -326,18 +326,22 @@ static void launch_cfg(int nblocks, hipStream_t st, const Linear& L, const float
 
 int linear_max_split() { return 16; }
 
-static constexpr int kBigMinRows = 320;  // rows from which the pre-split path is faster for the SwiGLU projection (measured)
+// Rows from which the SwiGLU projection is faster with its input pre-split (launch_linear_big).  In the fused
+// kernel every 256-column workgroup re-reads (and re-evaluates) gate and up for its K-slice: 8 bytes per element
+// against 4 for the pre-split terms, over twice as many workgroup columns.  Measured crossover: above 128 rows at
+// K = 14336, from 96 rows at K = 28672.
+static int big_min_rows_default(const Linear& L) { return L.K >= 16384 ? 96 : 129; }
 
-int linear_big_min_rows() {
+int linear_big_min_rows(const Linear& L) {
     const int v = tuning().linear_big_min_m;
-    return v == 0 ? kBigMinRows : (v < 0 ? INT32_MAX : v);
+    return v == 0 ? big_min_rows_default(L) : (v < 0 ? INT32_MAX : v);
 }
 
 int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
                       float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st) {
     if (ksplit_out) *ksplit_out = 1;
     if (M == 0) return CHIRON_OK;
-    if (asplit && prologue != PRO_PACKED && M >= linear_big_min_rows() && (prologue == PRO_SWIGLU || tuning().linear_big_all))
+    if (asplit && prologue != PRO_PACKED && M >= linear_big_min_rows(L) && (prologue == PRO_SWIGLU || tuning().linear_big_all))
         return launch_linear_big(L, A, lda, M, y, ldy, accumulate, prologue, part, max_split, ksplit_out, asplit, st);
     if (L.K % 16 != 0 || L.K < 16) return fail(CHIRON_ERR_SHAPE, "linear: K=%d must be a positive multiple of 16", L.K);
     if (prologue != PRO_PACKED && (lda % 4 != 0 || ((uintptr_t)A & 15)))
@@ -345,10 +349,15 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     const Tuning& tn = tuning();
     // Tile shape.  Up to 64 rows the kernel is HBM-bound: 32- or 64-row tiles; one column tile per wave when K can
     // be sliced (twice the workgroups along N, so half the K-slices for the consumer to add up) or when that is
-    // what it takes to give every CU a workgroup, else two.  From ~384 rows on it is
-    // matrix-core bound and the 128-row x 4-tile wave shape wins (fewer LDS reads and staging per MFMA), at one
-    // wave per SIMD; in between the 64-row shape measured faster.
-    const bool big = M >= 384;
+    // what it takes to give every CU a workgroup, else two.  With many rows it is matrix-core bound and the
+    // 128-row x 4-tile wave shape wins (fewer LDS reads and staging per MFMA, at one wave per SIMD): always from
+    // 384 rows, and earlier when 128-row tiles pad the rows no further than 64-row tiles do, from 96 rows for a
+    // very wide output (the LM head), 224 rows at K >= 8192 (measured on the 8B and 70B shapes).
+    const int tiles_n = L.Npad / 32;
+    const int pad64 = (M + 63) / 64 * 64, pad128 = (M + 127) / 128 * 128;
+    const int thr128 = tiles_n >= 2048 ? 96 : (L.K >= 8192 ? 224 : 384);
+    // (outputs narrower than 256 column tiles keep the 64-row shape at any row count: measured 8-12 % faster)
+    const bool big = tiles_n >= 256 && (M >= 384 || (pad128 == pad64 && M >= thr128));
     int mt = tn.linear_mt ? tn.linear_mt : (big ? 4 : (M > 32 ? 2 : 1));
     int tiles = L.Npad / 32;
     int gz = (M + 32 * mt - 1) / (32 * mt);
