@@ -26,9 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "b39421ddc5687632b9dc740417cb6a1a96ce05ee336a438b163b328c013f9fba", 275616722, 4894455),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "9c39d6c81bec1ad33ef7ed18d9ab07f00e5ce2bd3162ab315a9cd55ad9254f1d", 243392938, 7340032),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "9c39d6c81bec1ad33ef7ed18d9ab07f00e5ce2bd3162ab315a9cd55ad9254f1d", 125033033, 16777217),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "58006c770bc35d9ccb37c670a56bde7fb9d81650bfee2ecf402886d59d09df45", 275229291, 4261985),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "757e4ebc2f4a632a8e2f4c2414cdcc2c210fb0eede65c7ef00d731fcee2fab9b", 125032410, 16777216),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "757e4ebc2f4a632a8e2f4c2414cdcc2c210fb0eede65c7ef00d731fcee2fab9b", 243420502, 7340032),
 }
 
 
