@@ -25,8 +25,6 @@ int32_t fail(int32_t code, const char* fmt, ...) {
 
 // smallest max_batch for which the model carries the workspace of the large-batch projection kernel
 static constexpr int kBigWorkspaceMinBatch = 96;
-// bf16 elements between consecutive 32-row weight tiles beyond 32*Kpad (see Linear::tstride)
-static constexpr int kTilePad = 0;
 
 static int32_t dev_alloc(void** p, size_t bytes) {
     *p = nullptr;
@@ -45,8 +43,7 @@ static int32_t linear_alloc(Linear& L, int N, int K) {
     L.Npad = (N + 31) / 32 * 32;
     L.Kpad = (K + 127) / 128 * 128;
     L.owned = true;
-    const int pad = tuning().linear_tile_pad;
-    L.tstride = (size_t)32 * L.Kpad + (size_t)(pad < 0 ? kTilePad : pad / 8 * 8);
+    L.tstride = (size_t)32 * L.Kpad;
     const size_t bytes = (size_t)(L.Npad / 32) * L.tstride * 2;
     int32_t rc = dev_alloc((void**)&L.w, bytes);
     if (rc) return rc;
@@ -640,7 +637,7 @@ int32_t chiron_set_tuning(const char* key, int32_t value) {
     Tuning& t = tuning();
     struct { const char* k; int* p; } tab[] = {
         {"linear_nf", &t.linear_nf}, {"linear_mt", &t.linear_mt}, {"linear_xcd_remap", &t.linear_xcd_remap}, {"linear_ksplit", &t.linear_ksplit},
-        {"linear_target_blocks", &t.linear_target_blocks}, {"linear_big_min_m", &t.linear_big_min_m}, {"linear_big_all", &t.linear_big_all}, {"linear_ks", &t.linear_ks}, {"linear_tile_pad", &t.linear_tile_pad}, {"attn_grid", &t.attn_grid},
+        {"linear_target_blocks", &t.linear_target_blocks}, {"linear_big_min_m", &t.linear_big_min_m}, {"linear_big_all", &t.linear_big_all}, {"linear_ks", &t.linear_ks}, {"attn_grid", &t.attn_grid},
         {"attn_target_waves", &t.attn_target_waves}, {"attn_chunk_pages", &t.attn_chunk_pages}};
     for (auto& e : tab)
         if (!strcmp(e.k, key)) {

@@ -32,7 +32,7 @@ int32_t fail(int32_t code, const char* fmt, ...);
 struct Linear {
     uint16_t* w = nullptr;  // device, packed and zero-padded
     int N = 0, K = 0, Npad = 0, Kpad = 0;
-    size_t tstride = 0;  // elements from one 32-row tile to the next: 32*Kpad plus a pad that breaks the power of two
+    size_t tstride = 0;  // elements from one 32-row tile to the next (32*Kpad; padding it was measured to change nothing)
     bool owned = false;
 };
 
@@ -47,7 +47,6 @@ struct Tuning {
     int linear_ksplit = 0;          // forced number of K-slices
     int linear_target_blocks = 256; // K is sliced until the grid has about this many workgroups
     int linear_big_min_m = 0;       // rows from which the input is pre-split into tiled bf16 terms (0 = built-in, <0 = never)
-    int linear_tile_pad = -1;       // pad between weight tiles in bf16 elements, read when a matrix is packed (-1 = built-in)
     int linear_ks = 0;              // k-steps of 16 per chunk (depth of the weight ring): 4 or 8
     int linear_big_all = 0;         // 1: pre-split every projection's input from that row count on, not only the SwiGLU one
     int attn_grid = 0;              // workgroups of the persistent attention grid

@@ -356,6 +356,49 @@ def test_multi_token_step(m, T):
     assert e.value.code == -3
 
 
+def test_continuous_batching_over_several_iterations():
+    """The calls in the use the paper describes (Continuous Batching: requests join and leave the running batch between
+    iterations; the queue and its lengths are the caller's): eight requests start, every iteration feeds each running
+    request the token the oracle's greedy choice gave it and advances its length, some finish and others take
+    their place, lengths cross page boundaries.  Both sides run the same schedule from the same cache content;
+    every iteration's logits are compared."""
+    lens0 = np.array([13, 15, 30, 47, 5, 64, 0, 95], np.int32)
+    n_iter, grow = 7, 8
+    c = make_case(seed=21, storage="bf16", gain_jitter=0.1, seq_lens=lens0, pool_factor=3.0)
+    bt, nb = I.make_block_table(lens0 + grow, seed=21, pool_factor=3.0)   # pages for the tokens still to come
+    c.block_table, c.num_blocks = bt, nb
+    g = gpu_setup(c, poison=True)
+    opool = fresh_pool(c)
+    lens = lens0.copy()
+    toks = c.tokens.copy()
+    running = list(range(8))
+    for it in range(n_iter):
+        if it == 2:
+            running = [0, 2, 3, 5, 7]          # three requests finish
+        if it == 4:
+            running = [7, 1, 0, 4, 5, 6]       # two waiting ones (their caches kept) join, order changes
+        idx = np.asarray(running)
+        B().validate_step_inputs(g.model, g.pool, g.block_table[idx].contiguous(), torch.from_numpy(lens[idx]).cuda(),
+                                 torch.from_numpy(toks[idx]).cuda())
+        got = B().decode_step(g.model, g.pool, g.block_table[idx].contiguous(), torch.from_numpy(lens[idx]).cuda(),
+                              torch.from_numpy(toks[idx]).cuda()).cpu().numpy()
+        want, _ = orc.decode_step(c.cfg, c.w, opool, np.ascontiguousarray(bt[idx]), lens[idx], toks[idx])
+        print("iteration", it, "batch", running, flush=True)
+        check_logits(got, want, min_agree=1.0)
+        toks[idx] = want.argmax(1).astype(np.int32)   # greedy continuation, the same on both sides
+        lens[idx] += 1
+    assert lens.max() <= (lens0 + grow).max()
+    # the caches agree afterwards: old content bit-exact, generated positions to one bf16 ulp
+    for i in range(8):
+        k, v = g.pool.gather(1, g.block_table[i].contiguous(), int(lens[i]))
+        ok, ov = orc.gather_kv(opool, 1, bt[i], int(lens[i]))
+        L0 = int(lens0[i])
+        assert np.array_equal(bits(k)[:L0], ok[:L0]) and np.array_equal(bits(v)[:L0], ov[:L0])
+        fa, fb = bf16_to_f32(bits(k)[L0:]), bf16_to_f32(ok[L0:])
+        if fb.size:
+            assert np.all(np.abs(fa - fb) <= np.abs(fb) * 2.0 ** -6 + 2e-3 * np.abs(fb).max())
+
+
 def test_repeat_step_is_idempotent_and_profile_runs():
     c = make_case(batch=4, seed=6, storage="bf16")
     g, got, want, _ = run_both(c)
