@@ -50,7 +50,8 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // every later LDS read wait for all outstanding copies of this kind, which would undo the overlap; the caller
 // waits itself (s_waitcnt vmcnt, then a barrier) before anyone reads the destination.
 __device__ __forceinline__ void global_to_lds_16(const void* g, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr);  // the "s" constraint alone does not move a VGPR value
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(g) : "memory", "m0");
 }
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;

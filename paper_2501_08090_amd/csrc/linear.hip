@@ -158,19 +158,28 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
     };
     // PRO_PACKED: chunk c of the pre-split activations goes HBM/L2 -> LDS directly (16 bytes per lane, a wave
     // fills 64 consecutive rows of one k-group), no registers and no LDS store instructions in between
-    auto dma_a = [&](int c, uint4* dst_hi, uint4* dst_lo) {
-        constexpr int JOBS = KG * (MROWS / 64) * 2;  // (k-group, 64-row half, hi|lo) per chunk
-        static_assert(PRO != PRO_PACKED || (MROWS % 64 == 0 && JOBS % 4 == 0), "packed input needs 64-row halves");
+    constexpr int JOBS = KG * (MROWS / 64) * 2;  // (k-group, 64-row half, hi|lo) per chunk, dealt to the 4 waves
+    static_assert(PRO != PRO_PACKED || (MROWS % 64 == 0 && JOBS % 4 == 0), "packed input needs 64-row halves");
+    constexpr int WJOBS = PRO == PRO_PACKED ? JOBS / 4 : 1;
+    // per job: this lane's source at chunk 0 (it advances by one chunk of k-groups per chunk) and the wave-uniform
+    // LDS byte address of the job's destination in either buffer
+    const float4* dma_src[WJOBS];
+    uint32_t dma_dst[WJOBS];  // in buffer 0; buffer 1 lies KG*RS pieces further in both arrays
+    if (PRO == PRO_PACKED) {
 #pragma unroll
-        for (int j = 0; j < JOBS / 4; ++j) {
+        for (int j = 0; j < WJOBS; ++j) {
             const int job = wave + 4 * j;
             const int lo = job & 1, half = (job >> 1) % (MROWS / 64), kg = (job >> 1) / (MROWS / 64);
             const int m = half * 64 + lane;
-            const size_t idx = ((size_t)min(bz * MT + m / 32, mtiles_all - 1) * kgroups + (c * KG + kg)) * 32 + (m & 31);
-            const float4* g = (lo ? Alo : Ahi) + idx;
-            uint4* l = (lo ? dst_lo : dst_hi) + kg * RS + half * 64;
-            global_to_lds_16(g, __builtin_amdgcn_readfirstlane(lds_address(l)));
+            const size_t idx = ((size_t)min(bz * MT + m / 32, mtiles_all - 1) * kgroups + kg) * 32 + (m & 31);
+            dma_src[j] = (lo ? Alo : Ahi) + idx;
+            dma_dst[j] = __builtin_amdgcn_readfirstlane(lds_address((lo ? lds_lo[0] : lds_hi[0]) + kg * RS + half * 64));
         }
+    }
+    auto dma_a = [&](int c, int buf) {
+#pragma unroll
+        for (int j = 0; j < WJOBS; ++j)
+            global_to_lds_16(dma_src[j] + (size_t)c * (KG * 32), dma_dst[j] + (uint32_t)buf * (uint32_t)(KG * RS * sizeof(uint4)));
     };
     auto mma_step = [&](int buf, int s) {
         bf16x8 ah[MT], al[MT];
@@ -205,14 +214,14 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
                 load_w(c_begin, s);
                 __builtin_amdgcn_sched_barrier(0);  // same issue order as in the loop: k-step 0 is the oldest
             }
-            dma_a(c_begin, lds_hi[0], lds_lo[0]);
+            dma_a(c_begin, 0);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             lds_barrier();
             int buf = 0;
             for (int c = c_begin; c < c_last; ++c) {
                 // start the copy of chunk c+1 into the idle buffer (last read before the barrier that ended the
                 // previous round), multiply chunk c out of the other one while refilling the weight ring
-                dma_a(c + 1, lds_hi[buf ^ 1], lds_lo[buf ^ 1]);
+                dma_a(c + 1, buf ^ 1);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int s = 0; s < KS; ++s) {
