@@ -110,9 +110,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b-b64-lognormal800")
-    ap.add_argument("--sweep", action="store_true", help="time the batch-size sweep (prefixes of the batch); on by default for "
-                    "workloads of up to 64 requests, where it costs a fraction of a second")
-    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep (prefixes of the batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=32)
     ap.add_argument("--autoscale-slo-ms", type=float, default=0.0,
@@ -207,7 +205,7 @@ def main():
                          sum_of_kernel_ms=round(step_kernel_ms, 3)),
                kernels=kernels)
 
-    if (a.sweep or batch <= 64) and not a.no_sweep:
+    if a.sweep:
         sizes = [b for b in W.SWEEP_BATCHES if b <= batch]
         pts = B.step_latency_profile(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, sizes, warmup=2,
                                      iters=max(3, min(a.steps, 10)), logits=logits)
