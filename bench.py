@@ -26,9 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "58006c770bc35d9ccb37c670a56bde7fb9d81650bfee2ecf402886d59d09df45", 275229291, 4261985),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "757e4ebc2f4a632a8e2f4c2414cdcc2c210fb0eede65c7ef00d731fcee2fab9b", 125032410, 16777216),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "757e4ebc2f4a632a8e2f4c2414cdcc2c210fb0eede65c7ef00d731fcee2fab9b", 243420502, 7340032),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "58006c770bc35d9ccb37c670a56bde7fb9d81650bfee2ecf402886d59d09df45", 275229737, 4262091),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "8a66858313df3ffc866d6e31de1635af99df4058c4265d8be60bb86af4966d80", 125025147, 16777217),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "8a66858313df3ffc866d6e31de1635af99df4058c4265d8be60bb86af4966d80", 243420305, 7340032),
 }
 
 

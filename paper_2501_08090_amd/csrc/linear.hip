@@ -8,6 +8,9 @@
 // one K-slice each slice stores its partial product in a workspace [slice][M][N]; the kernel that
 // consumes the projection (residual add + RMSNorm, or RoPE) sums the slices while it reads them,
 // in a fixed order, so results are reproducible run to run.
+//
+// PRO_PACKED (large batches, see linear_big.hip): the activations arrive already split into their two bf16
+// terms in tile order and are copied global -> LDS directly, without staging registers or conversion work.
 #include <climits>
 #include <cstdlib>
 
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
             for (int r = 0; r < 16; ++r) acc[f][t][r] = 0.f;
 
     uint4 w[KS][NF];
-    float4 areg[TPT][2];  // PRO_PACKED: the hi and lo pieces as raw bits
+    float4 areg[TPT][2];  // fp32 staging registers (unused with PRO_PACKED, whose input goes straight into LDS)
     float4 ureg[PRO == PRO_SWIGLU ? TPT : 1][2];
     // PRO_PACKED: A points at the hi terms in 32-row x 8-k tile order, the lo terms follow them
     const int mtiles_all = (M + 31) / 32;
@@ -110,9 +113,6 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
     };
     auto load_a = [&](int c) {
         int kbase = c * KC;
-        if (PRO == PRO_PACKED) {
-            return;
-        }
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
             int task = tid + i * 256;
@@ -129,9 +129,6 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
     };
     auto stage_a = [&](int c, int buf) {
         int kbase = c * KC;
-        if (PRO == PRO_PACKED) {
-            return;
-        }
 #pragma unroll
         for (int i = 0; i < TPT; ++i) {
             int task = tid + i * 256;
