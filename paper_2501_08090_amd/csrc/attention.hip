@@ -188,8 +188,8 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                 const uint16_t* tile = lbase + ((size_t)blk * n_kv + c) * (2 * tile_elems);
 #pragma unroll
                 for (int s = 0; s < KSTEPS; ++s) {
-                    kk[u][s] = *reinterpret_cast<const uint4*>(tile + (size_t)(s * 64 + lane) * 8);
-                    vv[u][s] = *reinterpret_cast<const uint4*>(tile + tile_elems + (size_t)(s * 64 + lane) * 8);
+                    kk[u][s] = load_stream_16(tile + (size_t)(s * 64 + lane) * 8);
+                    vv[u][s] = load_stream_16(tile + tile_elems + (size_t)(s * 64 + lane) * 8);
                 }
             }
         };

@@ -45,6 +45,15 @@ __device__ __forceinline__ float wave_sum(float v) {
 // flight (weight prefetch) stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// 16-byte load of data that is read exactly once (K/V tiles, weights when a single workgroup row streams them):
+// the non-temporal hint keeps such streams from displacing the L2's working set and measured 8-12 % more
+// streaming bandwidth than plain loads (7.0 against 6.3 TB/s at 512 workgroups).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream_16(const void* p) {
+    u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // 16 bytes per lane straight from global memory into LDS: lane l's piece lands at lds_addr + 16*l (lds_addr is
 // the wave-uniform byte address inside the workgroup's LDS).  Written as assembly on purpose: the compiler makes
 // every later LDS read wait for all outstanding copies of this kind, which would undo the overlap; the caller
