@@ -26,9 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "58006c770bc35d9ccb37c670a56bde7fb9d81650bfee2ecf402886d59d09df45", 275229737, 4262091),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "8a66858313df3ffc866d6e31de1635af99df4058c4265d8be60bb86af4966d80", 125025147, 16777217),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "8a66858313df3ffc866d6e31de1635af99df4058c4265d8be60bb86af4966d80", 243420305, 7340032),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "fef514fc256f31647b498938bb2b90610df2b0dec5f656e9589f7ae628126054", 275720685, 4259907),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "8a66858313df3ffc866d6e31de1635af99df4058c4265d8be60bb86af4966d80", 125025278, 16777216),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "8a66858313df3ffc866d6e31de1635af99df4058c4265d8be60bb86af4966d80", 243420532, 7340032),
 }
 
 
