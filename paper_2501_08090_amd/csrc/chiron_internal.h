@@ -42,7 +42,7 @@ enum Prologue { PRO_NONE = 0, PRO_SWIGLU = 1, PRO_PACKED = 2 };
 // Performance knobs (0 = built-in heuristic); see chiron_set_tuning.
 struct Tuning {
     int linear_nf = 0;              // 32-column tiles per wave (1 or 2)
-    int linear_mt = 0;              // 32-row tiles per workgroup (1, 2 or 4)
+    int linear_mt = 0;              // 32-row tiles per workgroup (1, 2, 3 or 4)
     int linear_xcd_remap = 1;       // deal logical workgroup ids XCD by XCD (M-tiles of one weight tile share an L2)
     int linear_ksplit = 0;          // forced number of K-slices
     int linear_target_blocks = 256; // K is sliced until the grid has about this many workgroups

@@ -364,7 +364,9 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     const int thr128 = tiles_n >= 2048 ? 96 : (L.K >= 8192 ? 224 : 384);
     // (outputs narrower than 256 column tiles keep the 64-row shape at any row count: measured 8-12 % faster)
     const bool big = tiles_n >= 256 && (M >= 384 || (pad128 == pad64 && M >= thr128));
-    int mt = tn.linear_mt ? tn.linear_mt : (big ? 4 : (M > 32 ? 2 : 1));
+    // 65..96 rows take one 96-row tile: with 64-row tiles the second M-tile would stream every weight again for a
+    // handful of rows (a step of 17 % in the whole decode step's latency between batch 64 and 65)
+    int mt = tn.linear_mt ? tn.linear_mt : (big ? 4 : (M > 64 && M <= 96 ? 3 : (M > 32 ? 2 : 1)));
     int tiles = L.Npad / 32;
     int gz = (M + 32 * mt - 1) / (32 * mt);
     int nf = tn.linear_nf ? tn.linear_nf
@@ -378,11 +380,12 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
         nf = tn.linear_nf ? (tn.linear_nf == 4 ? 4 : 2) : (tiles >= 128 ? 4 : 2);
     }
     if (nf == 4 && mt == 1) mt = 2;
+    if (nf == 4 && mt == 3) mt = 4;  // four column tiles per wave are built for 64- and 128-row tiles only
     gz = (M + 32 * mt - 1) / (32 * mt);  // mt may have changed above
     int gx = (tiles + 4 * nf - 1) / (4 * nf);
     // A projection that cannot slice K (no workspace) runs one workgroup per CU; a ring of 8 k-steps then keeps twice
     // the weight bytes in flight per wave, which measured 9 % faster on the gate/up shape at 64 rows.
-    const bool ks8 = mt == 2 && nf <= 2 && prologue != PRO_PACKED &&
+    const bool ks8 = (mt == 2 || (mt == 3 && nf == 1 && prologue == PRO_NONE)) && nf <= 2 && prologue != PRO_PACKED &&
                      (tn.linear_ks == 8 || (tn.linear_ks == 0 && nf == 1 && !part && prologue == PRO_NONE));
     const int KC = ks8 ? 128 : 64;
     int chunks = (L.K + KC - 1) / KC;
@@ -405,7 +408,9 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
         else                                                                                                            \
             launch_cfg<MT_, NF_, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz); \
     } while (0)
-    if (ks8) {
+    if (ks8 && mt == 3) {
+        launch_cfg<3, 1, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+    } else if (ks8) {
         if (prologue == PRO_SWIGLU) launch_cfg<2, 2, PRO_SWIGLU, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else if (nf == 1) launch_cfg<2, 1, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else launch_cfg<2, 2, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
@@ -419,6 +424,8 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     else if (mt == 1) CHIRON_LAUNCH(1, 2);
     else if (mt == 2 && nf == 1) CHIRON_LAUNCH(2, 1);
     else if (mt == 2) CHIRON_LAUNCH(2, 2);
+    else if (mt == 3 && nf == 1) CHIRON_LAUNCH(3, 1);
+    else if (mt == 3) CHIRON_LAUNCH(3, 2);
     else if (nf == 1) CHIRON_LAUNCH(4, 1);
     else CHIRON_LAUNCH(4, 2);
 #undef CHIRON_LAUNCH

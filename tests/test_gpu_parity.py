@@ -128,7 +128,7 @@ def test_rmsnorm(rows, n):
 
 @pytest.mark.parametrize("M,N,K", [(1, 256, 256), (4, 512, 256), (4, 1376, 256), (4, 256, 688), (33, 96, 1040),
                                    (64, 1024, 4096), (100, 160, 512), (130, 4096, 1024), (7, 1000, 64),
-                                   (400, 8192, 512), (385, 2080, 256)])
+                                   (400, 8192, 512), (385, 2080, 256), (70, 512, 256), (96, 1376, 4096), (65, 4096, 512)])
 def test_linear(M, N, K):
     rng = np.random.default_rng(M * 7 + N * 3 + K)
     x = rng.standard_normal((M, K)).astype(np.float32)
@@ -146,7 +146,7 @@ def test_linear(M, N, K):
     lin.close()
 
 
-@pytest.mark.parametrize("M,N,K", [(4, 256, 688), (64, 512, 1408), (40, 96, 64), (390, 512, 704)])
+@pytest.mark.parametrize("M,N,K", [(4, 256, 688), (64, 512, 1408), (40, 96, 64), (390, 512, 704), (80, 512, 704), (96, 96, 64)])
 def test_swiglu_linear(M, N, K):
     rng = np.random.default_rng(M + N + K)
     gu = (rng.standard_normal((M, 2 * K)) * 2).astype(np.float32)
