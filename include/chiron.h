@@ -162,9 +162,9 @@ int32_t chiron_decode_step(chiron_model *m, chiron_kvpool *p, const int32_t *blo
  * causally over positions 0..seq_lens[i]+t, the K/V of all q_len tokens are written (their pages must be in
  * the block table), and logits[i][t] are the next-token logits after token t.
  *   tokens dev int32 [batch, q_len];  logits dev fp32 [batch, q_len, vocab];  batch*q_len <= max_batch.
- * q_len == 1 is chiron_decode_step.  The projections run over batch*q_len rows.  In attention the q_len tokens
- * of a request share one pass over its pages while (query heads per KV head) * q_len <= 16 (the operand columns
- * of the attention kernel); for longer blocks every row attends on its own (the pages are then read q_len times). */
+ * q_len == 1 is chiron_decode_step.  The projections run over batch*q_len rows.  In attention as many tokens of
+ * a request as fit the kernel's 16 operand columns (16 / query heads per KV head: 4 at the 8B geometry, 2 at
+ * 70B's) share one pass over its pages; longer blocks take ceil(q_len / that many) passes. */
 int32_t chiron_decode_step_multi(chiron_model *m, chiron_kvpool *p, const int32_t *block_table, const int32_t *seq_lens,
                                  const int32_t *tokens, int32_t batch, int32_t q_len, float *logits, void *stream);
 

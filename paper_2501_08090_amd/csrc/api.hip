@@ -292,10 +292,11 @@ static int32_t check_step_args(const chiron_model* m, const chiron_kvpool* p, co
 // One pass of the model over B rows.  Row r carries token tokens[r] at position seq_lens[r] of the request whose
 // pages block_table row r lists.  With q_len == 1 a row is a request.  With q_len > 1 rows r = i*q_len + t are the
 // new tokens of request i (expanded index arrays), and attention runs per request over (req_bt, req_lens, B/q_len):
-// one pass over a request's pages serves its q_len tokens.
+// a pass over a request's pages serves as many of its q_len tokens as fit the attention kernel's operand columns.
 static int32_t step_rows(chiron_model* m, chiron_kvpool* p, const int32_t* block_table, const int32_t* seq_lens,
                          const int32_t* tokens, int32_t B, const int32_t* req_bt, const int32_t* req_lens, int32_t q_len,
                          float* logits, hipStream_t st) {
+    const AttnShape ash = attn_shape(m->cfg.n_q_heads / m->cfg.n_kv_heads, q_len, q_len);
     int32_t rc;
     const chiron_model_config& c = m->cfg;
     const int H = c.hidden, d = c.head_dim, F = c.ffn, qn = c.n_q_heads * d, kn = c.n_kv_heads * d;
@@ -310,17 +311,18 @@ static int32_t step_rows(chiron_model* m, chiron_kvpool* p, const int32_t* block
             CHIRON_HIP(hipEventCreate(&tm.b));                                   \
             CHIRON_HIP(hipEventRecord(tm.a, st));                                \
         }                                                                        \
-        if ((rc = (expr))) return rc;                                            \
+        rc = (expr);                                                             \
         if (m->timing) {                                                         \
-            CHIRON_HIP(hipEventRecord(tm.b, st));                                \
-            m->timed.push_back(tm);                                              \
+            (void)hipEventRecord(tm.b, st);                                      \
+            m->timed.push_back(tm); /* owned by the model from here on */        \
         }                                                                        \
+        if (rc) return rc;                                                       \
     } while (0)
     const int msplit = linear_max_split();
     int ks_res = 0, ks_qkv = 1;  // K-slices waiting in m->part for the residual stream / of the QKV projection
     STEP(CHIRON_K_OTHER, launch_embed(m->embed, tokens, B, H, m->h, st));
     STEP(CHIRON_K_OTHER, launch_rope_table(seq_lens, B, d, c.rope_base, m->cos_t, m->sin_t, st));
-    STEP(CHIRON_K_OTHER, launch_attn_plan(m->aws, req_lens, q_len, n_req, c.n_kv_heads, q_len, st));
+    STEP(CHIRON_K_OTHER, launch_attn_plan(m->aws, req_lens, ash, n_req, c.n_kv_heads, st));
     for (int l = 0; l < c.n_layers; ++l) {
         // h += (slices of the previous down projection); x = norm(h)
         STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->attn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
@@ -328,8 +330,8 @@ static int32_t step_rows(chiron_model* m, chiron_kvpool* p, const int32_t* block
         STEP(CHIRON_K_ROPE_APPEND,
              launch_rope_append(p->d, l, ks_qkv > 1 ? m->part : m->qkvb, ks_qkv, c.n_q_heads, m->cos_t, m->sin_t, block_table,
                                 mb, seq_lens, B, m->qb, st));
-        STEP(CHIRON_K_ATTN, launch_attn_main(m->aws, p->d, l, m->qb, qn, c.n_q_heads, req_bt, mb, req_lens, q_len, n_req, q_len, st));
-        STEP(CHIRON_K_ATTN_MERGE, launch_attn_merge(m->aws, p->d, c.n_q_heads, n_req, q_len, m->attn, qn, st));
+        STEP(CHIRON_K_ATTN, launch_attn_main(m->aws, p->d, l, m->qb, qn, c.n_q_heads, req_bt, mb, req_lens, ash, n_req, st));
+        STEP(CHIRON_K_ATTN_MERGE, launch_attn_merge(m->aws, p->d, c.n_q_heads, ash, n_req, m->attn, qn, st));
         STEP(CHIRON_K_O, launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, m->part, msplit, &ks_res, m->asplit, st));
         if (ks_res == 1) ks_res = 0;  // written straight into h
         STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->ffn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
@@ -365,16 +367,12 @@ int32_t chiron_decode_step_multi(chiron_model* m, chiron_kvpool* p, const int32_
     if (batch == 0) return CHIRON_OK;
     // rows (i, t) share request i's pages; row t sees the K/V that rows t' <= t append in the same layer, because
     // every layer appends all rows before its attention starts
+    if (!logits) return fail(CHIRON_ERR_INVALID_ARG, "logits is null");
     rc = launch_expand_rows(block_table, seq_lens, batch, q_len, m->cfg.max_blocks_per_seq, m->x_bt, m->x_lens,
                             (hipStream_t)stream);
     if (rc) return rc;
-    if (!logits) return fail(CHIRON_ERR_INVALID_ARG, "logits is null");
-    // when the q_len tokens' query heads fit the 16 operand columns of the attention kernel, a request's pages are
-    // read once for all of them; otherwise every row attends on its own
-    const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
-    if (G * q_len <= 16)
-        return step_rows(m, p, m->x_bt, m->x_lens, tokens, batch * q_len, block_table, seq_lens, q_len, logits, (hipStream_t)stream);
-    return step_rows(m, p, m->x_bt, m->x_lens, tokens, batch * q_len, m->x_bt, m->x_lens, 1, logits, (hipStream_t)stream);
+    // attention runs per request: its pages are read once per group of as many tokens as fit the 16 operand columns
+    return step_rows(m, p, m->x_bt, m->x_lens, tokens, batch * q_len, block_table, seq_lens, q_len, logits, (hipStream_t)stream);
 }
 
 static int32_t check_inputs_host(const chiron_model_config* cfg, int32_t num_blocks, int32_t block_size,
@@ -472,9 +470,10 @@ int32_t chiron_step_latency_profile(chiron_model* m, chiron_kvpool* p, const int
         int32_t rc = check_step_args(m, p, block_table, seq_lens, tokens, b);
         if (rc) return rc;
     }
-    std::vector<hipEvent_t> ev((size_t)iters + 1);
-    for (auto& e : ev) CHIRON_HIP(hipEventCreate(&e));
+    std::vector<hipEvent_t> ev((size_t)iters + 1, nullptr);
     int32_t rc = CHIRON_OK;
+    for (auto& e : ev)
+        if (rc == CHIRON_OK && hipEventCreate(&e) != hipSuccess) rc = fail(CHIRON_ERR_HIP, "profile: cannot create an event");
     for (int k = 0; k < n_sizes && rc == CHIRON_OK; ++k) {
         int b = batch_sizes[k];
         for (int w = 0; w < warmup && rc == CHIRON_OK; ++w)
@@ -504,7 +503,8 @@ int32_t chiron_step_latency_profile(chiron_model* m, chiron_kvpool* p, const int
         out[k].lat_ms_mean = sum / iters;
         out[k].tokens_per_s = b / (out[k].lat_ms_median * 1e-3);
     }
-    for (auto& e : ev) (void)hipEventDestroy(e);
+    for (auto& e : ev)
+        if (e) (void)hipEventDestroy(e);
     return rc;
 }
 
@@ -603,12 +603,13 @@ int32_t chiron_op_paged_attention(chiron_model* m, const chiron_kvpool* p, int32
     if (!q || !block_table || !ctx_lens || !out) return fail(CHIRON_ERR_INVALID_ARG, "attention: a pointer is null");
     hipStream_t st = (hipStream_t)stream;
     const int qn = m->cfg.n_q_heads * m->cfg.head_dim;
-    int32_t rc = launch_attn_plan(m->aws, ctx_lens, 0, batch, m->cfg.n_kv_heads, 1, st);
+    const AttnShape sh = attn_shape(m->cfg.n_q_heads / m->cfg.n_kv_heads, 1, 0);
+    int32_t rc = launch_attn_plan(m->aws, ctx_lens, sh, batch, m->cfg.n_kv_heads, st);
     if (rc) return rc;
-    rc = launch_attn_main(m->aws, p->d, layer, q, qn, m->cfg.n_q_heads, block_table, m->cfg.max_blocks_per_seq, ctx_lens,
-                          0, batch, 1, st);
+    rc = launch_attn_main(m->aws, p->d, layer, q, qn, m->cfg.n_q_heads, block_table, m->cfg.max_blocks_per_seq, ctx_lens, sh,
+                          batch, st);
     if (rc) return rc;
-    return launch_attn_merge(m->aws, p->d, m->cfg.n_q_heads, batch, 1, out, qn, st);
+    return launch_attn_merge(m->aws, p->d, m->cfg.n_q_heads, sh, batch, out, qn, st);
 }
 
 int32_t chiron_local_autoscale_step(double itl, double itl_slo, double tput_prev, double tput_curr, double alpha,

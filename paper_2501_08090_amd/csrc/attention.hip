@@ -13,6 +13,7 @@
 // The work list is built on the device from seq_lens (the host never sees the lengths), and the
 // attention grid is persistent: each wave strides over the list, which has a fixed length in
 // memory, so every wave terminates.
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <type_traits>
@@ -23,15 +24,31 @@
 namespace chiron {
 
 // plan buffer layout (int32): [0] n_items, [1] chunk_pages, [2..3] unused,
-// [4, 4+max_batch) first item of request i, [.., +max_batch) number of items of request i,
-// then item_seq[cap_items], item_pg0[cap_items]
+// [4, 4+max_batch) first item of pass v, [.., +max_batch) number of items of pass v,
+// then item_seq[cap_items] (the pass), item_pg0[cap_items].  A pass v = request * ng + token group (AttnShape).
 int64_t attn_plan_ints(int max_batch, int cap_items) { return 4 + 2 * (int64_t)max_batch + 2 * (int64_t)cap_items; }
+
+AttnShape attn_shape(int G, int q_len, int len_bias) {
+    AttnShape sh;
+    sh.q_len = q_len;
+    sh.tg = std::min(q_len, std::max(1, 16 / G));
+    sh.ng = (q_len + sh.tg - 1) / sh.tg;
+    sh.bias0 = len_bias - q_len;
+    return sh;
+}
+
+// positions attended by pass v (its last token's view)
+__device__ __forceinline__ int pass_len(const int32_t* __restrict__ seq_lens, const AttnShape& sh, int v) {
+    const int i = v / sh.ng, g = v - i * sh.ng;
+    return seq_lens[i] + sh.bias0 + g * sh.tg + min(sh.tg, sh.q_len - g * sh.tg);
+}
 
 constexpr int kPlanThreads = 1024;
 
 __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __restrict__ plan, int max_batch, int cap_items,
-                                                                 const int32_t* __restrict__ seq_lens, int len_bias,
+                                                                 const int32_t* __restrict__ seq_lens, AttnShape sh,
                                                                  int batch, int n_kv, int slots, int target_waves, int force_cp, int item_limit) {
+    batch *= sh.ng;  // passes
     __shared__ int scan[kPlanThreads];
     int32_t* seq_item0 = plan + 4;
     int32_t* seq_nch = plan + 4 + max_batch;
@@ -54,11 +71,11 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     };
     auto count_items = [&](int cp) {
         int n = 0;
-        for (int i = i0; i < i1; ++i) n += ((seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize + cp - 1) / cp;
+        for (int i = i0; i < i1; ++i) n += ((pass_len(seq_lens, sh, i) + kBlockSize - 1) / kBlockSize + cp - 1) / cp;
         return block_sum(n);
     };
     int pages = 0;
-    for (int i = i0; i < i1; ++i) pages += (seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize;
+    for (int i = i0; i < i1; ++i) pages += (pass_len(seq_lens, sh, i) + kBlockSize - 1) / kBlockSize;
     const int total = block_sum(pages);
 
     // Pages per item.  A wave takes items w, w + slots, ...: if the list is only a little longer than the number of
@@ -86,7 +103,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     // exclusive scan of items per request
     int items = 0;
     for (int i = i0; i < i1; ++i) {
-        int np = (seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize;
+        int np = (pass_len(seq_lens, sh, i) + kBlockSize - 1) / kBlockSize;
         items += (np + cp - 1) / cp;
     }
     scan[tid] = items;
@@ -99,7 +116,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     }
     int off = scan[tid] - items;
     for (int i = i0; i < i1; ++i) {
-        int np = (seq_lens[i] + len_bias + kBlockSize - 1) / kBlockSize;
+        int np = (pass_len(seq_lens, sh, i) + kBlockSize - 1) / kBlockSize;
         int nch = (np + cp - 1) / cp;
         seq_item0[i] = off;
         seq_nch[i] = nch;
@@ -115,25 +132,25 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     }
 }
 
-int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv, int q_len,
-                         hipStream_t st) {
+int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const AttnShape& sh, int batch, int n_kv, hipStream_t st) {
     const Tuning& t = tuning();
+    if ((int64_t)batch * sh.ng > ws.max_batch) return fail(CHIRON_ERR_BATCH_TOO_LARGE, "attention: %d requests x %d token groups exceed the workspace", batch, sh.ng);
     const int slots = 4 * (t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);  // waves of the persistent attention grid
-    attn_plan_kernel<<<1, kPlanThreads, 0, st>>>(ws.plan, ws.max_batch, ws.cap_items, seq_lens, len_bias, batch, n_kv, slots,
+    attn_plan_kernel<<<1, kPlanThreads, 0, st>>>(ws.plan, ws.max_batch, ws.cap_items, seq_lens, sh, batch, n_kv, slots,
                                                   t.attn_target_waves > 0 ? t.attn_target_waves : 4 * slots, t.attn_chunk_pages,
-                                                  ws.cap_items / q_len);  // a partial result holds q_len tokens' heads
+                                                  ws.cap_items / sh.tg);  // a partial result holds tg tokens' heads
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
 
 // ---- the attention kernel ---------------------------------------------------------------------------
-// MULTI: every request brings T = q_len new tokens (rows i*T .. i*T+T-1 of q), all already appended; operand column
-// t*G + g is query head g of token t, which sees positions < len - (T-1) + t.  One pass over the request's pages
-// serves all T tokens (G*T <= 16 columns).
+// MULTI: every request brings q_len new tokens (rows i*q_len .. of q), all already appended.  A pass serves one token
+// group of tv <= tg tokens: operand column t*G + h is query head h of the group's token t, which sees positions
+// < len - (tv-1) + t of the pass's len; the request's pages are read once per pass (G*tg <= 16 columns).
 template <int D, int G, bool MULTI>
-__global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, const float* __restrict__ q, int ldq, int T,
+__global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, const float* __restrict__ q, int ldq, AttnShape sh,
                                                          const int32_t* __restrict__ bt, int max_blocks,
-                                                         const int32_t* __restrict__ seq_lens, int len_bias,
+                                                         const int32_t* __restrict__ seq_lens,
                                                          const int32_t* __restrict__ plan, int max_batch, int cap_items,
                                                          float* __restrict__ part_o, float* __restrict__ part_ml,
                                                          float scale_log2e) {
@@ -148,21 +165,24 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
     const int32_t* item_seq = plan + 4 + 2 * max_batch;
     const int32_t* item_pg0 = item_seq + cap_items;
     const int head = lane & 15, lg = lane >> 4;
-    const int cols = MULTI ? G * T : G;              // live operand columns
+    const int pcols = MULTI ? G * sh.tg : G;         // columns of a partial result
     const int tq = MULTI ? head / G : 0, hq = MULTI ? head % G : head;
     const size_t tile_elems = (size_t)16 * D;
 
     // item metadata (request, first page, length) is fetched one item ahead
     int w = blockIdx.x * 4 + wave;
-    int i_nx = 0, pg0_nx = 0, len_nx = 0;
+    int v_nx = 0, pg0_nx = 0, len_nx = 0;
     if (w < n_work) {
-        i_nx = __builtin_amdgcn_readfirstlane(item_seq[w / n_kv]);
+        v_nx = __builtin_amdgcn_readfirstlane(item_seq[w / n_kv]);
         pg0_nx = __builtin_amdgcn_readfirstlane(item_pg0[w / n_kv]);
-        len_nx = __builtin_amdgcn_readfirstlane(seq_lens[i_nx]) + len_bias;
+        len_nx = __builtin_amdgcn_readfirstlane(pass_len(seq_lens, sh, v_nx));
     }
     for (; w < n_work; w += n_waves) {
         const int it = w / n_kv, c = w - it * n_kv;
-        const int i = i_nx, pg0 = pg0_nx, len = len_nx;
+        const int pg0 = pg0_nx, len = len_nx;
+        const int i = MULTI ? v_nx / sh.ng : v_nx, g = MULTI ? v_nx - i * sh.ng : 0;
+        const int tv = MULTI ? min(sh.tg, sh.q_len - g * sh.tg) : 1;  // tokens of this pass
+        const int cols = G * tv;                                       // live operand columns
         const int npages = (len + kBlockSize - 1) / kBlockSize;
         const int pg1 = min(pg0 + cp, npages);
         const int32_t* btrow = bt + (size_t)i * max_blocks;
@@ -210,7 +230,7 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                 }
                 if (TAIL) {
                     const int len_eff = (pg + u < pg1) ? len : 0;
-                    const int len_col = MULTI ? min(len_eff, len - (T - 1) + tq) : len_eff;  // causal among the new tokens
+                    const int len_col = MULTI ? min(len_eff, len - (tv - 1) + tq) : len_eff;  // causal among the new tokens
                     const int tok0 = (pg + u) * 16 + lg * 4;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) s[u][r] = (tok0 + r < len_col) ? s[u][r] : -INFINITY;
@@ -269,16 +289,16 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
         {
             const int wn = w + n_waves;  // next item's metadata, needed only after this item is done
             if (wn < n_work) {
-                i_nx = __builtin_amdgcn_readfirstlane(item_seq[wn / n_kv]);
+                v_nx = __builtin_amdgcn_readfirstlane(item_seq[wn / n_kv]);
                 pg0_nx = __builtin_amdgcn_readfirstlane(item_pg0[wn / n_kv]);
-                len_nx = __builtin_amdgcn_readfirstlane(seq_lens[i_nx]) + len_bias;
+                len_nx = __builtin_amdgcn_readfirstlane(pass_len(seq_lens, sh, v_nx));
             }
         }
         // q fragments: operand column = head, 8 consecutive dims per lane group; scaled by log2(e)/sqrt(d)
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
             if (head < cols) {
-                const float* qp = q + (size_t)(MULTI ? i * T + tq : i) * ldq + (size_t)(c * G + hq) * D + s * 32 + lg * 8;
+                const float* qp = q + (size_t)(MULTI ? i * sh.q_len + g * sh.tg + tq : i) * ldq + (size_t)(c * G + hq) * D + s * 32 + lg * 8;
                 float4 a = *reinterpret_cast<const float4*>(qp), b = *reinterpret_cast<const float4*>(qp + 4);
                 split2(a.x * scale_log2e, a.y * scale_log2e, qh[s].x, ql[s].x);
                 split2(a.z * scale_log2e, a.w * scale_log2e, qh[s].y, ql[s].y);
@@ -309,7 +329,7 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
         l_run += __shfl_xor(l_run, 16);
         l_run += __shfl_xor(l_run, 32);
         if (head < cols) {
-            const size_t slot = (size_t)w * cols + head;
+            const size_t slot = (size_t)w * pcols + head;
             if (lg == 0) {
                 part_ml[slot * 2] = MULTI ? fmaxf(m_run, -1e30f) : m_run;
                 part_ml[slot * 2 + 1] = l_run;
@@ -325,17 +345,19 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
 // 256 threads = 8 item slices x 32 lanes of float4 (D = 128) or 16 slices x 16 lanes (D = 64); slice k takes
 // items k, k+S, ...; the slices are combined through LDS in a fixed order.
 template <int D>
-__global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restrict__ plan, int max_batch, int n_kv, int G, int T,
+__global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restrict__ plan, int max_batch, int n_kv, int G, AttnShape sh,
                                                           const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml, float* __restrict__ out,
                                                           int ldo) {
     constexpr int LANES = D / 4, S = 256 / LANES;
     __shared__ float4 s_num[S][LANES];
     __shared__ float s_den[S], s_max[S];
-    // row = request * T + token; a partial result holds G*T columns per (item, kv head), column = token*G + head
-    const int row = blockIdx.x, i = row / T, tq = row % T, a = blockIdx.y, c = a / G, j = tq * G + a % G, GT = G * T;
+    // row = request * q_len + token; the token's pass v = request * ng + token / tg; a partial result holds G*tg
+    // columns per (item, kv head), column = (token % tg) * G + head
+    const int row = blockIdx.x, t = row % sh.q_len, v = row / sh.q_len * sh.ng + t / sh.tg;
+    const int a = blockIdx.y, c = a / G, j = (t % sh.tg) * G + a % G, GT = G * sh.tg;
     const int sl = threadIdx.x / LANES, ln = threadIdx.x % LANES;
-    const int item0 = plan[4 + i], nch = plan[4 + max_batch + i];
+    const int item0 = plan[4 + v], nch = plan[4 + max_batch + v];
     // each slice folds its items with a running maximum, two items' loads in flight at a time
     float M = -INFINITY, den = 0.f;
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -385,19 +407,19 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restr
 }
 
 template <int D>
-static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p, int layer, const float* q, int ldq, int T,
-                             const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias,
+static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p, int layer, const float* q, int ldq,
+                             const AttnShape& sh, const int32_t* bt, int max_blocks, const int32_t* seq_lens,
                              const AttnWorkspace& ws, float scale) {
 #define CHIRON_ATTN(G_)                                                                                              \
     do {                                                                                                             \
-        if (T > 1)                                                                                                   \
-            paged_attn_kernel<D, G_, true><<<grid, 256, 0, st>>>(p, layer, q, ldq, T, bt, max_blocks, seq_lens,      \
-                                                                 len_bias, ws.plan, ws.max_batch, ws.cap_items,      \
-                                                                 ws.part_o, ws.part_ml, scale);                      \
+        if (sh.q_len > 1)                                                                                            \
+            paged_attn_kernel<D, G_, true><<<grid, 256, 0, st>>>(p, layer, q, ldq, sh, bt, max_blocks, seq_lens,     \
+                                                                 ws.plan, ws.max_batch, ws.cap_items, ws.part_o,     \
+                                                                 ws.part_ml, scale);                                 \
         else                                                                                                         \
-            paged_attn_kernel<D, G_, false><<<grid, 256, 0, st>>>(p, layer, q, ldq, 1, bt, max_blocks, seq_lens,     \
-                                                                  len_bias, ws.plan, ws.max_batch, ws.cap_items,     \
-                                                                  ws.part_o, ws.part_ml, scale);                     \
+            paged_attn_kernel<D, G_, false><<<grid, 256, 0, st>>>(p, layer, q, ldq, sh, bt, max_blocks, seq_lens,    \
+                                                                  ws.plan, ws.max_batch, ws.cap_items, ws.part_o,    \
+                                                                  ws.part_ml, scale);                                \
     } while (0)
     switch (G) {
         case 1: CHIRON_ATTN(1); break;
@@ -412,30 +434,32 @@ static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p
 }
 
 int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
-                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch, int q_len,
+                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, const AttnShape& sh, int batch,
                          hipStream_t st) {
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
-    if (q_len < 1 || G * q_len > 16) return fail(CHIRON_ERR_INVALID_ARG, "attention: %d tokens x %d heads per KV head exceed 16 operand columns", q_len, G);
+    if (sh.q_len < 1 || sh.tg < 1 || G * sh.tg > 16 || sh.ng != (sh.q_len + sh.tg - 1) / sh.tg)
+        return fail(CHIRON_ERR_INVALID_ARG, "attention: %d tokens in groups of %d x %d heads per KV head do not fit 16 operand columns",
+                    sh.q_len, sh.tg, G);
     const float scale = (float)(1.4426950408889634 / std::sqrt((double)p.d));
     const Tuning& t = tuning();
     dim3 grid(t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);
     int32_t rc;
-    if (p.d == 128) rc = launch_attn_d<128>(G, grid, st, p, layer, q, ldq, q_len, bt, max_blocks, seq_lens, len_bias, ws, scale);
-    else if (p.d == 64) rc = launch_attn_d<64>(G, grid, st, p, layer, q, ldq, q_len, bt, max_blocks, seq_lens, len_bias, ws, scale);
+    if (p.d == 128) rc = launch_attn_d<128>(G, grid, st, p, layer, q, ldq, sh, bt, max_blocks, seq_lens, ws, scale);
+    else if (p.d == 64) rc = launch_attn_d<64>(G, grid, st, p, layer, q, ldq, sh, bt, max_blocks, seq_lens, ws, scale);
     else return fail(CHIRON_ERR_SHAPE, "attention: head_dim must be 64 or 128 (got %d)", p.d);
     if (rc) return rc;
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
 
-int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, int batch, int q_len, float* out, int ldo,
-                          hipStream_t st) {
+int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, const AttnShape& sh, int batch, float* out,
+                          int ldo, hipStream_t st) {
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
-    dim3 rgrid(batch * q_len, n_q);
-    if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, q_len, ws.part_o, ws.part_ml, out, ldo);
-    else attn_reduce_kernel<64><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, q_len, ws.part_o, ws.part_ml, out, ldo);
+    dim3 rgrid(batch * sh.q_len, n_q);
+    if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
+    else attn_reduce_kernel<64><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }

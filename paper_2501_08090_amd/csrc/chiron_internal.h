@@ -110,21 +110,28 @@ int32_t launch_rope_append(const PoolDesc& p, int layer, const float* qkv, int k
 // ---- paged attention ------------------------------------------------------------------------------
 struct AttnWorkspace {
     int32_t* plan = nullptr;     // [0]=n_items, [1]=chunk_pages; then per-seq and per-item tables (see attention.hip)
-    float* part_o = nullptr;     // [cap_items*n_kv][G][d]
-    float* part_ml = nullptr;    // [cap_items*n_kv][G][2]
+    float* part_o = nullptr;     // [items*n_kv][tg*G][d], items*tg <= cap_items
+    float* part_ml = nullptr;    // [items*n_kv][tg*G][2]
     int cap_items = 0, max_batch = 0;
 };
 int64_t attn_plan_ints(int max_batch, int cap_items);
-// builds the work list for attend lengths len_i = seq_lens[i] + len_bias
-// q_len > 1: each request brings q_len new tokens (already appended; len_bias = q_len) that share one pass over its
-// pages: q and out hold rows request*q_len + token, token t sees positions <= seq_lens[i] + t.  n_q/n_kv * q_len <= 16.
-int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, int len_bias, int batch, int n_kv, int q_len,
-                         hipStream_t st);
+// How the q_len new tokens of a request map onto passes of the attention kernel.  The kernel has 16 operand columns:
+// a pass serves tg tokens x G query heads of one KV head (tg*G <= 16) while reading the request's pages once, so a
+// request is attended in ng = ceil(q_len / tg) passes ("token groups"); group g holds tokens g*tg .. and attends
+// len(i, g) = seq_lens[i] + bias0 + g*tg + (tokens in g) positions, token t of the request seeing positions
+// <= seq_lens[i] + bias0 + t.  q and out hold rows request*q_len + token.  q_len = 1: one group, len = seq_lens + bias0 + 1.
+struct AttnShape {
+    int q_len = 1, tg = 1, ng = 1, bias0 = 0;
+};
+// len_bias: what to add to seq_lens[i] for the number of positions the LAST new token attends (q_len when all new
+// tokens are appended and seq_lens counts only the older ones; 0 when seq_lens is already the attended length)
+AttnShape attn_shape(int G, int q_len, int len_bias);
+int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const AttnShape& sh, int batch, int n_kv, hipStream_t st);
 int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
-                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, int len_bias, int batch, int q_len,
+                         const int32_t* bt, int max_blocks, const int32_t* seq_lens, const AttnShape& sh, int batch,
                          hipStream_t st);
-int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, int batch, int q_len, float* out, int ldo,
-                          hipStream_t st);
+int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, const AttnShape& sh, int batch, float* out,
+                          int ldo, hipStream_t st);
 
 }  // namespace chiron
 

@@ -321,15 +321,17 @@ def test_decode_step_medium_shape_d128():
 
 
 G4_D128 = dict(I.TINY, head_dim=128, n_kv_heads=2, n_q_heads=8)
+G8_D128 = dict(I.TINY, head_dim=128, n_kv_heads=1, n_q_heads=8)
 
 
-@pytest.mark.parametrize("m,T", [(I.TINY, 2), (I.TINY, 4), (I.TINY, 8), (I.TINY, 9), (G4_D128, 4), (G4_D128, 3), (G4_D128, 5)])
+@pytest.mark.parametrize("m,T", [(I.TINY, 2), (I.TINY, 4), (I.TINY, 8), (I.TINY, 9), (I.TINY, 17), (G4_D128, 4), (G4_D128, 3),
+                                 (G4_D128, 5), (G4_D128, 8), (G4_D128, 11), (G8_D128, 2), (G8_D128, 5)])
 def test_multi_token_step(m, T):
     """q_len > 1 (speculative-decoding verify shape): causal over the block, all T tokens' K/V appended.
-    While heads-per-KV-head x T <= 16 the T tokens share one pass over the request's pages (operand columns
-    token*G + head); beyond that every row attends on its own.  Lengths 15, 31, 63 put the first new token at
-    the end of a page / of a work item, so that later tokens open a page or an item in which the earlier ones
-    see nothing."""
+    As many tokens as fit the 16 operand columns (16 / heads-per-KV-head) share one pass over the request's pages
+    (operand columns token*G + head); longer blocks take several passes, the last one ragged (9 = 8+1, 17 = 8+8+1,
+    11 = 4+4+3, 5 = 2+2+1).  Lengths 15, 31, 63 put the first new token at the end of a page / of a work item, so
+    that later tokens open a page or an item in which the earlier ones see nothing."""
     lens = [14, 15, 31, 63, 60, 0, 127, 1]
     c = make_case(m=m, seed=16, storage="bf16", gain_jitter=0.1, seq_lens=lens, pool_factor=3.0)
     toks = I.token_ids(len(lens) * T, c.m["vocab"], 6).reshape(len(lens), T)
