@@ -26,9 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "fef514fc256f31647b498938bb2b90610df2b0dec5f656e9589f7ae628126054", 275720685, 4259907),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "8a66858313df3ffc866d6e31de1635af99df4058c4265d8be60bb86af4966d80", 125025278, 16777216),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "8a66858313df3ffc866d6e31de1635af99df4058c4265d8be60bb86af4966d80", 243420532, 7340032),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "5517162f668de8505dea43d020c74f0d06887264ddac8955060268df7641907a", 275673940, 4259905),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "74ffc6a2da5164067e1138b2e987a35c90c41512f3994c29e5f264d8e2f9f55e", 125032189, 16777217),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "74ffc6a2da5164067e1138b2e987a35c90c41512f3994c29e5f264d8e2f9f55e", 243422121, 7340032),
 }
 
 
