@@ -5,8 +5,8 @@
 
 A "step" is one chiron_decode_step (every kernel of the path) over one batch of seeded synthetic
 requests whose weights, cache and index arrays are already resident in HBM.  Prints ONE JSON line:
-whole-job decode tokens/s, the roofline position of the dominant kernel (HIP-event timed inside the
-library around each launch), and the CPU oracle timed on the host cores on a bounded sample of the
+whole-job decode tokens/s, the roofline position of the dominant kernel (timed with the start/stop HIP
+events that the library attaches to each kernel launch), and the CPU oracle timed on the host cores on a bounded sample of the
 same workload.  Everything runs on one GPU; --gpus above 1 is refused.
 """
 import argparse
@@ -26,9 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "5517162f668de8505dea43d020c74f0d06887264ddac8955060268df7641907a", 275673940, 4259905),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "74ffc6a2da5164067e1138b2e987a35c90c41512f3994c29e5f264d8e2f9f55e", 125032189, 16777217),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "74ffc6a2da5164067e1138b2e987a35c90c41512f3994c29e5f264d8e2f9f55e", 243422121, 7340032),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "5cc3acd476d891c81f999335841d322104d79e6d539ae39fbda894929e790e69", 275682878, 4259915),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "b3db40dee64ffae4694809a7c82f18c6533b054980bdf184c6571499ab49987e", 125032498, 16777216),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "b3db40dee64ffae4694809a7c82f18c6533b054980bdf184c6571499ab49987e", 243422701, 7340032),
 }
 
 
@@ -161,7 +161,7 @@ def main():
     tokens_per_s = batch / sec
     log("step %.3f ms, %.0f tokens/s" % (sec * 1e3, tokens_per_s))
 
-    # per-kernel event timing (separate steps: the events sit between the launches)
+    # per-kernel timing from the launches' own start/stop events (separate steps: timed launches cost host time)
     kt = kernel_times(B, wl, batch, max(2, min(a.steps, 10)), logits)
     alg = kernel_algorithmic(m, batch, wl.context_tokens)
     kernels = {}

@@ -223,11 +223,13 @@ int32_t chiron_step_latency_profile(chiron_model *m, chiron_kvpool *p, const int
 int32_t chiron_local_autoscale_step(double itl, double itl_slo, double tput_prev, double tput_curr, double alpha,
                                     int32_t batch_limit, int32_t *max_batch, double *backpressure_out);
 
-/* Measurement aid: between _begin and _end every kernel launch of chiron_decode_step on this
- * model is bracketed by HIP events on the step's stream; _end synchronises `stream` and returns,
- * per kernel class, the summed event time and the number of launches since _begin.  (The QKV,
- * O, gate/up, down and LM-head projections are instances of one kernel; a projection whose
- * partial sums need a cleared output counts that clear in its class.) */
+/* Measurement aid: between _begin and _end every kernel that chiron_decode_step[_multi] launches for this
+ * model from the calling thread carries a start and a stop event of its own (hipExtLaunchKernelGGL): they read
+ * the begin and end timestamps of the dispatch, the same ones a profiler's kernel trace reports, and add nothing
+ * to the stream between kernels.  _end synchronises `stream` and returns, per kernel class, the summed kernel
+ * time and the number of launches since _begin.  (The QKV, O, gate/up, down and LM-head projections are
+ * instances of one kernel; a projection of many rows that first splits its input counts as one launch and its
+ * time is the sum of its two kernels.) */
 enum {
     CHIRON_K_QKV = 0, CHIRON_K_O, CHIRON_K_GATEUP, CHIRON_K_DOWN, CHIRON_K_LMHEAD, CHIRON_K_ATTN, CHIRON_K_ATTN_MERGE,
     CHIRON_K_RMSNORM, CHIRON_K_ROPE_APPEND, CHIRON_K_OTHER, CHIRON_K_COUNT

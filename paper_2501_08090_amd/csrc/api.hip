@@ -15,6 +15,11 @@ namespace chiron {
 
 static thread_local char g_err[512] = "";
 
+TimingScope*& timing_scope() {
+    static thread_local TimingScope* scope = nullptr;
+    return scope;
+}
+
 int32_t fail(int32_t code, const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
@@ -302,21 +307,19 @@ static int32_t step_rows(chiron_model* m, chiron_kvpool* p, const int32_t* block
     const int H = c.hidden, d = c.head_dim, F = c.ffn, qn = c.n_q_heads * d, kn = c.n_kv_heads * d;
     const int n_req = B / q_len;
     const int mb = c.max_blocks_per_seq;
-    // each launch is optionally bracketed by events (chiron_kernel_timing_begin/end)
-#define STEP(cls, expr)                                                          \
-    do {                                                                         \
-        chiron_model::Timed tm{cls, nullptr, nullptr};                           \
-        if (m->timing) {                                                         \
-            CHIRON_HIP(hipEventCreate(&tm.a));                                   \
-            CHIRON_HIP(hipEventCreate(&tm.b));                                   \
-            CHIRON_HIP(hipEventRecord(tm.a, st));                                \
-        }                                                                        \
-        rc = (expr);                                                             \
-        if (m->timing) {                                                         \
-            (void)hipEventRecord(tm.b, st);                                      \
-            m->timed.push_back(tm); /* owned by the model from here on */        \
-        }                                                                        \
-        if (rc) return rc;                                                       \
+    // while kernel timing is on, the kernels of each launch carry their own start/stop events (see launch())
+    TimingScope scope;
+    scope.sink = &m->timed;
+    struct ScopeGuard {
+        bool on;
+        explicit ScopeGuard(TimingScope* s) : on(s != nullptr) { if (on) timing_scope() = s; }
+        ~ScopeGuard() { if (on) timing_scope() = nullptr; }
+    } guard(m->timing ? &scope : nullptr);
+#define STEP(cls_, expr)              \
+    do {                              \
+        scope.cls = (cls_);           \
+        scope.first = true;           \
+        if ((rc = (expr))) return rc; \
     } while (0)
     const int msplit = linear_max_split();
     int ks_res = 0, ks_qkv = 1;  // K-slices waiting in m->part for the residual stream / of the QKV projection
@@ -671,7 +674,7 @@ int32_t chiron_kernel_timing_end(chiron_model* m, void* stream, chiron_kernel_ti
         float ms = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, t.a, t.b);
         out[t.cls].ms += ms;
-        out[t.cls].launches += 1;
+        out[t.cls].launches += t.first ? 1 : 0;
         (void)hipEventDestroy(t.a);
         (void)hipEventDestroy(t.b);
     }

@@ -136,7 +136,7 @@ int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const
     const Tuning& t = tuning();
     if ((int64_t)batch * sh.ng > ws.max_batch) return fail(CHIRON_ERR_BATCH_TOO_LARGE, "attention: %d requests x %d token groups exceed the workspace", batch, sh.ng);
     const int slots = 4 * (t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);  // waves of the persistent attention grid
-    attn_plan_kernel<<<1, kPlanThreads, 0, st>>>(ws.plan, ws.max_batch, ws.cap_items, seq_lens, sh, batch, n_kv, slots,
+    launch(attn_plan_kernel, dim3(1), dim3(kPlanThreads), st, ws.plan, ws.max_batch, ws.cap_items, seq_lens, sh, batch, n_kv, slots,
                                                   t.attn_target_waves > 0 ? t.attn_target_waves : 4 * slots, t.attn_chunk_pages,
                                                   ws.cap_items / sh.tg);  // a partial result holds tg tokens' heads
     CHIRON_HIP(hipGetLastError());
@@ -413,11 +413,11 @@ static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p
 #define CHIRON_ATTN(G_)                                                                                              \
     do {                                                                                                             \
         if (sh.q_len > 1)                                                                                            \
-            paged_attn_kernel<D, G_, true><<<grid, 256, 0, st>>>(p, layer, q, ldq, sh, bt, max_blocks, seq_lens,     \
+            launch(paged_attn_kernel<D, G_, true>, dim3(grid), dim3(256), st, p, layer, q, ldq, sh, bt, max_blocks, seq_lens,     \
                                                                  ws.plan, ws.max_batch, ws.cap_items, ws.part_o,     \
                                                                  ws.part_ml, scale);                                 \
         else                                                                                                         \
-            paged_attn_kernel<D, G_, false><<<grid, 256, 0, st>>>(p, layer, q, ldq, sh, bt, max_blocks, seq_lens,    \
+            launch(paged_attn_kernel<D, G_, false>, dim3(grid), dim3(256), st, p, layer, q, ldq, sh, bt, max_blocks, seq_lens,    \
                                                                   ws.plan, ws.max_batch, ws.cap_items, ws.part_o,    \
                                                                   ws.part_ml, scale);                                \
     } while (0)
@@ -458,8 +458,8 @@ int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, c
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
     dim3 rgrid(batch * sh.q_len, n_q);
-    if (p.d == 128) attn_reduce_kernel<128><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
-    else attn_reduce_kernel<64><<<rgrid, 256, 0, st>>>(ws.plan, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
+    if (p.d == 128) launch(attn_reduce_kernel<128>, dim3(rgrid), dim3(256), st, ws.plan, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
+    else launch(attn_reduce_kernel<64>, dim3(rgrid), dim3(256), st, ws.plan, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }

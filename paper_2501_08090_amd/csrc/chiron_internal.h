@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <vector>
@@ -23,6 +24,36 @@ int32_t fail(int32_t code, const char* fmt, ...);
         if (_e != hipSuccess)                                                                 \
             return ::chiron::fail(CHIRON_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(_e)); \
     } while (0)
+
+// ---- kernel launches, optionally timed -------------------------------------------------------------
+// While a timing scope is open on the calling thread (chiron_kernel_timing_begin .. end), every launch carries a
+// start and a stop event of its own (hipExtLaunchKernelGGL): they read the dispatch's begin and end timestamps, the
+// same ones a profiler's kernel trace shows, and put nothing between the kernels.  Otherwise a plain launch.
+struct TimedLaunch {
+    int cls;      // chiron_kernel_class
+    bool first;   // first kernel of a step's launch (a launch may consist of two kernels)
+    hipEvent_t a, b;
+};
+struct TimingScope {
+    std::vector<TimedLaunch>* sink = nullptr;
+    int cls = 0;
+    bool first = true;
+};
+TimingScope*& timing_scope();  // thread-local; null when no scope is open
+
+template <typename... P, typename... A>
+inline void launch(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, A... args) {
+    TimingScope* ts = timing_scope();
+    hipEvent_t a = nullptr, b = nullptr;
+    if (ts && hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess) {
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, a, b, 0, static_cast<P>(args)...);
+        ts->sink->push_back(TimedLaunch{ts->cls, ts->first, a, b});
+        ts->first = false;
+        return;
+    }
+    if (a) (void)hipEventDestroy(a);
+    kernel<<<grid, block, 0, st>>>(static_cast<P>(args)...);
+}
 
 // ---- packed linear layer --------------------------------------------------------------------------
 // Weight W [N,K] (out,in) is stored as 32-row tiles, each tile as K/8 groups of [32 rows][8 k] bf16:
@@ -160,10 +191,6 @@ struct chiron_model {
     float *cos_t = nullptr, *sin_t = nullptr;
     chiron::AttnWorkspace aws;
     // optional per-kernel event timing of decode steps
-    struct Timed {
-        int cls;
-        hipEvent_t a, b;
-    };
     bool timing = false;
-    std::vector<Timed> timed;
+    std::vector<chiron::TimedLaunch> timed;
 };

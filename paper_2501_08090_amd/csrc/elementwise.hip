@@ -24,7 +24,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const uint16_t* __restrict__
 
 int32_t launch_embed(const uint16_t* table, const int32_t* tokens, int batch, int H, float* h, hipStream_t st) {
     if (batch == 0) return CHIRON_OK;
-    embed_kernel<<<batch, 256, 0, st>>>(table, tokens, H, h);
+    launch(embed_kernel, dim3(batch), dim3(256), st, table, tokens, H, h);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -94,10 +94,10 @@ int32_t launch_rmsnorm(float* h, const float* part, int ks, const uint16_t* gain
     if (rows == 0) return CHIRON_OK;
     if (n % 4 != 0 || n > 16384) return fail(CHIRON_ERR_SHAPE, "rmsnorm: n=%d must be a multiple of 4, <= 16384", n);
     size_t ps = (size_t)rows * n;
-    if (n <= 1024) rmsnorm_kernel<256, 1><<<rows, 256, 0, st>>>(h, part, ks, ps, gain, n, eps, out);
-    else if (n <= 4096) rmsnorm_kernel<1024, 1><<<rows, 1024, 0, st>>>(h, part, ks, ps, gain, n, eps, out);
-    else if (n <= 8192) rmsnorm_kernel<1024, 2><<<rows, 1024, 0, st>>>(h, part, ks, ps, gain, n, eps, out);
-    else rmsnorm_kernel<1024, 4><<<rows, 1024, 0, st>>>(h, part, ks, ps, gain, n, eps, out);
+    if (n <= 1024) launch(rmsnorm_kernel<256, 1>, dim3(rows), dim3(256), st, h, part, ks, ps, gain, n, eps, out);
+    else if (n <= 4096) launch(rmsnorm_kernel<1024, 1>, dim3(rows), dim3(1024), st, h, part, ks, ps, gain, n, eps, out);
+    else if (n <= 8192) launch(rmsnorm_kernel<1024, 2>, dim3(rows), dim3(1024), st, h, part, ks, ps, gain, n, eps, out);
+    else launch(rmsnorm_kernel<1024, 4>, dim3(rows), dim3(1024), st, h, part, ks, ps, gain, n, eps, out);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -116,7 +116,7 @@ int32_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
     int blocks = (int)((n4 + 255) / 256);
     if (blocks < 1) blocks = 1;
     if (blocks > 2048) blocks = 2048;
-    fill_zero_kernel<<<blocks, 256, 0, st>>>(reinterpret_cast<float4*>(p), n4, p, n);
+    launch(fill_zero_kernel, dim3(blocks), dim3(256), st, reinterpret_cast<float4*>(p), n4, p, n);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -139,7 +139,7 @@ __global__ void rope_table_kernel(const int32_t* __restrict__ pos, int rows, int
 int32_t launch_rope_table(const int32_t* pos, int rows, int d, float base, float* cos_t, float* sin_t, hipStream_t st) {
     if (rows == 0) return CHIRON_OK;
     int n = rows * (d / 2);
-    rope_table_kernel<<<(n + 255) / 256, 256, 0, st>>>(pos, rows, d, base, 0, cos_t, sin_t);
+    launch(rope_table_kernel, dim3((n + 255) / 256), dim3(256), st, pos, rows, d, base, 0, cos_t, sin_t);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void rope_kernel(float* __restrict__ x, int ld
 int32_t launch_rope(float* x, int ldx, int n_heads, int d, const float* cos_t, const float* sin_t, int rows,
                     hipStream_t st) {
     if (rows == 0) return CHIRON_OK;
-    rope_kernel<<<rows, 256, 0, st>>>(x, ldx, n_heads, d, cos_t, sin_t);
+    launch(rope_kernel, dim3(rows), dim3(256), st, x, ldx, n_heads, d, cos_t, sin_t);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -200,7 +200,7 @@ int32_t launch_append_kv(const PoolDesc& p, int layer, const uint16_t* k, const 
                          int max_blocks, const int32_t* seq_idx, const int32_t* pos, int64_t n, hipStream_t st) {
     if (n == 0) return CHIRON_OK;
     int blocks = (int)(n < 65536 ? n : 65536);
-    append_kv_kernel<<<blocks, 256, 0, st>>>(p, layer, k, v, bt, max_blocks, seq_idx, pos, n);
+    launch(append_kv_kernel, dim3(blocks), dim3(256), st, p, layer, k, v, bt, max_blocks, seq_idx, pos, n);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void gather_kv_kernel(PoolDesc p, int layer, c
 int32_t launch_gather_kv(const PoolDesc& p, int layer, const int32_t* bt_row, int len, uint16_t* k_out, uint16_t* v_out,
                          hipStream_t st) {
     if (len == 0) return CHIRON_OK;
-    gather_kv_kernel<<<len < 65536 ? len : 65536, 256, 0, st>>>(p, layer, bt_row, len, k_out, v_out);
+    launch(gather_kv_kernel, dim3(len < 65536 ? len : 65536), dim3(256), st, p, layer, bt_row, len, k_out, v_out);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256) void expand_rows_kernel(const int32_t* __restr
 int32_t launch_expand_rows(const int32_t* bt, const int32_t* seq_lens, int batch, int q_len, int max_blocks, int32_t* bt_out,
                            int32_t* lens_out, hipStream_t st) {
     if (batch * q_len == 0) return CHIRON_OK;
-    expand_rows_kernel<<<batch * q_len, 256, 0, st>>>(bt, seq_lens, q_len, max_blocks, bt_out, lens_out);
+    launch(expand_rows_kernel, dim3(batch * q_len), dim3(256), st, bt, seq_lens, q_len, max_blocks, bt_out, lens_out);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void swap_kernel(PoolDesc p, const int32_t* __
 
 int32_t launch_swap(const PoolDesc& p, const int32_t* bt_row, int n_pages, uint16_t* image, int to_image, hipStream_t st) {
     if (n_pages == 0) return CHIRON_OK;
-    swap_kernel<<<dim3(n_pages, p.n_layers), 256, 0, st>>>(p, bt_row, image, to_image);
+    launch(swap_kernel, dim3(dim3(n_pages, p.n_layers)), dim3(256), st, p, bt_row, image, to_image);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -322,7 +322,7 @@ int32_t launch_rope_append(const PoolDesc& p, int layer, const float* qkv, int k
     if (batch == 0) return CHIRON_OK;
     size_t stride = (size_t)batch * (n_q + 2 * p.n_kv) * p.d;
     dim3 grid(batch, n_q + 2 * p.n_kv);
-    rope_append_kernel<<<grid, 64, 0, st>>>(p, layer, qkv, ks, stride, n_q, cos_t, sin_t, bt, max_blocks, seq_lens, q_out);
+    launch(rope_append_kernel, dim3(grid), dim3(64), st, p, layer, qkv, ks, stride, n_q, cos_t, sin_t, bt, max_blocks, seq_lens, q_out);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }

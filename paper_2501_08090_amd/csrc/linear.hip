@@ -37,7 +37,7 @@ int32_t launch_pack_rows(const uint16_t* src, int rows, int K, size_t tstride, u
     if (rows == 0) return CHIRON_OK;
     int64_t total = (int64_t)rows * (K / 8);
     int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
-    pack_rows_kernel<<<blocks, 256, 0, st>>>(src, rows, K, tstride, dst_packed, row_offset);
+    launch(pack_rows_kernel, dim3(blocks), dim3(256), st, src, rows, K, tstride, dst_packed, row_offset);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
 
 int32_t launch_reduce_partials(const float* part, int ks, int64_t n, float* y, int accumulate, hipStream_t st) {
     int blocks = (int)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
-    reduce_partials_kernel<<<blocks, 256, 0, st>>>(part, ks, (size_t)n, n, y, accumulate);
+    launch(reduce_partials_kernel, dim3(blocks), dim3(256), st, part, ks, (size_t)n, n, y, accumulate);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -326,7 +326,7 @@ Tuning& tuning() {
 template <int MT, int NF, int PRO, int KS = 4>
 static void launch_cfg(int nblocks, hipStream_t st, const Linear& L, const float* A, int lda, int M, float* y, int ldy,
                        int cps, int mode, size_t part_stride, int gx, int gy, int gz) {
-    linear_kernel<MT, NF, KS, PRO><<<nblocks, 256, 0, st>>>(L.w, L.tstride, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode,
+    launch(linear_kernel<MT, NF, KS, PRO>, dim3(nblocks), dim3(256), st, L.w, L.tstride, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode,
                                                            part_stride, gx, gy, gz, tuning().linear_xcd_remap);
 }
 

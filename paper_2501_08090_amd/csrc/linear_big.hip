@@ -54,8 +54,8 @@ int32_t launch_linear_big(const Linear& L, const float* A, int lda, int M, float
     const int mtiles = (M + 31) / 32, kgroups = L.Kpad / 8;
     {
         dim3 grid((unsigned)((kgroups / 8 < 64) ? (kgroups + 7) / 8 : 64), (unsigned)mtiles);
-        if (prologue == PRO_SWIGLU) split_pack_kernel<PRO_SWIGLU><<<grid, 256, 0, st>>>(A, lda, M, L.K, L.Kpad, ah, al);
-        else split_pack_kernel<PRO_NONE><<<grid, 256, 0, st>>>(A, lda, M, L.K, L.Kpad, ah, al);
+        if (prologue == PRO_SWIGLU) launch(split_pack_kernel<PRO_SWIGLU>, dim3(grid), dim3(256), st, A, lda, M, L.K, L.Kpad, ah, al);
+        else launch(split_pack_kernel<PRO_NONE>, dim3(grid), dim3(256), st, A, lda, M, L.K, L.Kpad, ah, al);
         CHIRON_HIP(hipGetLastError());
     }
     return launch_linear(L, reinterpret_cast<const float*>(ah), 0, M, y, ldy, accumulate, PRO_PACKED, part, max_split, ksplit_out,
