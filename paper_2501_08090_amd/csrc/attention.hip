@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
         cp = 64;
         while (cp > 8 && (int64_t)(total / cp) * n_kv < target_waves) cp >>= 1;
     }
-    while (total / cp + batch > item_limit) cp <<= 1;
+    while (cp < (1 << 24) && total / cp + batch > item_limit) cp <<= 1;  // the host has checked that batch < item_limit
     if (force_cp > 0 && total / force_cp + batch <= item_limit) cp = force_cp;
     __syncthreads();
 
@@ -136,6 +136,8 @@ int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const
     const Tuning& t = tuning();
     if ((int64_t)batch * sh.ng > ws.max_batch) return fail(CHIRON_ERR_BATCH_TOO_LARGE, "attention: %d requests x %d token groups exceed the workspace", batch, sh.ng);
     const int slots = 4 * (t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);  // waves of the persistent attention grid
+    if ((int64_t)batch * sh.ng >= ws.cap_items / sh.tg)
+        return fail(CHIRON_ERR_BATCH_TOO_LARGE, "attention: %d passes do not fit a work list of %d items", batch * sh.ng, ws.cap_items / sh.tg);
     launch(attn_plan_kernel, dim3(1), dim3(kPlanThreads), st, ws.plan, ws.max_batch, ws.cap_items, seq_lens, sh, batch, n_kv, slots,
                                                   t.attn_target_waves > 0 ? t.attn_target_waves : 4 * slots, t.attn_chunk_pages,
                                                   ws.cap_items / sh.tg);  // a partial result holds tg tokens' heads

@@ -334,9 +334,9 @@ int linear_max_split() { return 16; }
 
 // Rows from which the SwiGLU projection is faster with its input pre-split (launch_linear_big).  In the fused
 // kernel every 256-column workgroup re-reads (and re-evaluates) gate and up for its K-slice: 8 bytes per element
-// against 4 for the pre-split terms, over twice as many workgroup columns.  Measured crossover: above 128 rows at
-// K = 14336, from 96 rows at K = 28672.
-static int big_min_rows_default(const Linear& L) { return L.K >= 16384 ? 96 : 129; }
+// against 4 for the pre-split terms, over twice as many workgroup columns.  Measured crossover: above 96 rows at
+// K = 14336 (45 against 51 us at 112 and 128 rows), from 96 rows at K = 28672.
+static int big_min_rows_default(const Linear& L) { return L.K >= 16384 ? 96 : 97; }
 
 int linear_big_min_rows(const Linear& L) {
     const int v = tuning().linear_big_min_m;
@@ -365,19 +365,28 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     // (outputs narrower than 256 column tiles keep the 64-row shape at any row count: measured 8-12 % faster)
     const bool big = tiles_n >= 256 && (M >= 384 || (pad128 == pad64 && M >= thr128));
     // 65..96 rows take one 96-row tile: with 64-row tiles the second M-tile would stream every weight again for a
-    // handful of rows (a step of 17 % in the whole decode step's latency between batch 64 and 65)
-    int mt = tn.linear_mt ? tn.linear_mt : (big ? 4 : (M > 64 && M <= 96 ? 3 : (M > 32 ? 2 : 1)));
+    // handful of rows (a step of 17 % in the whole decode step's latency between batch 64 and 65).  Likewise above
+    // 128 rows wherever 96-row tiles pad the rows no further than 64-row tiles do (129..192, 257..288, 321..384:
+    // a third fewer passes over the weights; measured 10-20 % on the gate/up and O projections).
+    const int pad96 = (M + 95) / 96 * 96;
+    int mt = tn.linear_mt ? tn.linear_mt : (big ? 4 : (M > 64 && pad96 <= pad64 ? 3 : (M > 32 ? 2 : 1)));
     int tiles = L.Npad / 32;
     int gz = (M + 32 * mt - 1) / (32 * mt);
+    // Column tiles per wave of a projection that cannot slice K: two as soon as that still gives about one workgroup
+    // per CU (224 for a 57344-wide gate/up: 190 against 260 us at 65 rows with hidden size 8192), else one
     int nf = tn.linear_nf ? tn.linear_nf
                           : (big && tiles >= 256 ? 4
-                             : ((!part && ((tiles + 7) / 8) * gz < kNumCU) || tiles < 64 || (part && M <= 64) ? 1 : 2));
+                             : ((!part && ((tiles + 7) / 8) * gz < 200) || tiles < 64 || (part && M <= 64) ? 1 : 2));
     // (MT=2, NF=1, KS=4, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
     // (the KS=8 build of it compiles but measured slower than two tiles per wave: 45 vs 36 us at 64 rows)
     if (prologue == PRO_SWIGLU) nf = 2;
     if (prologue == PRO_PACKED) {  // only the large-batch shapes are built for pre-split input
         mt = 4;
-        nf = tn.linear_nf ? (tn.linear_nf == 4 ? 4 : 2) : (tiles >= 128 ? 4 : 2);
+        // four column tiles per wave unless K-slicing cannot make up for the smaller grid (one 128-row tile of a
+        // 4096-wide output: 8 workgroup columns x 16 slices = half the chip; 58 against 45 us)
+        const int gx4 = (tiles + 15) / 16, gz4 = (M + 127) / 128;
+        const bool fills = !part || (int64_t)gx4 * gz4 * max_split >= 200;
+        nf = tn.linear_nf ? (tn.linear_nf == 4 ? 4 : 2) : (tiles >= 128 && fills ? 4 : 2);
     }
     if (nf == 4 && mt == 1) mt = 2;
     if (nf == 4 && mt == 3) mt = 4;  // four column tiles per wave are built for 64- and 128-row tiles only
@@ -390,6 +399,10 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     const int KC = ks8 ? 128 : 64;
     int chunks = (L.K + KC - 1) / KC;
     int ksplit = tn.linear_ksplit ? tn.linear_ksplit : (tn.linear_target_blocks + gx * gz - 1) / (gx * gz);
+    // shapes that run one workgroup per CU must not spill a few workgroups into a second round of the chip
+    // (264 workgroups took 141 us where 240 take 100)
+    const bool one_per_cu = mt * nf > 8 || (mt == 4 && prologue != PRO_NONE);
+    if (!tn.linear_ksplit && one_per_cu && gx * gz * ksplit > kNumCU && gx * gz <= kNumCU) ksplit = kNumCU / (gx * gz);
     if (ksplit > chunks / 2) ksplit = chunks / 2;
     if (ksplit > max_split) ksplit = max_split;
     if (!part) ksplit = 1;
