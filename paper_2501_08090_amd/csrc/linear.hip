@@ -113,7 +113,9 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
     auto load_w = [&](int c, int s) {
         size_t off = (size_t)(c * KC + s * 16) * 32;
 #pragma unroll
-        for (int f = 0; f < NF; ++f) w[s][f] = *reinterpret_cast<const uint4*>(wp[f] + off);
+        // non-temporal: a step reads every weight once, and what the weights do not displace stays cached for the
+        // activations and the K/V pages (same-device A/B on the whole step: -7 % at 1 request, -1.5 % at 64..2048)
+        for (int f = 0; f < NF; ++f) w[s][f] = load_stream_16(wp[f] + off);
     };
     // staging task i of a chunk: 8 consecutive k of one row, thread tid + 256*i
     auto load_task = [&](int c, int i, float4 (&ar)[2], float4 (&ur)[2]) {
