@@ -466,10 +466,10 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     const int KC = ks8 ? 128 : 64;
     int chunks = (L.K + KC - 1) / KC;
     int ksplit = tn.linear_ksplit ? tn.linear_ksplit : (tn.linear_target_blocks + gx * gz - 1) / (gx * gz);
-    // shapes that run one workgroup per CU must not spill a few workgroups into a second round of the chip
-    // (264 workgroups took 141 us where 240 take 100)
-    const bool one_per_cu = mt * nf > 8 || (mt == 4 && prologue != PRO_NONE);
-    if (!tn.linear_ksplit && one_per_cu && gx * gz * ksplit > kNumCU && gx * gz <= kNumCU) ksplit = kNumCU / (gx * gz);
+    // never a few workgroups more than one per CU: the CUs that get a second one take twice as long (264 workgroups
+    // of the one-per-CU shape took 141 us where 240 take 100; the QKV projection at 64 rows 20.7 us with 288
+    // workgroups, 16.2 us with 240)
+    if (!tn.linear_ksplit && gx * gz * ksplit > kNumCU && gx * gz <= kNumCU) ksplit = kNumCU / (gx * gz);
     if (ksplit > chunks / 2) ksplit = chunks / 2;
     if (ksplit > max_split) ksplit = max_split;
     if (!part) ksplit = 1;
