@@ -26,9 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "5cc3acd476d891c81f999335841d322104d79e6d539ae39fbda894929e790e69", 275681930, 4259896),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "b3db40dee64ffae4694809a7c82f18c6533b054980bdf184c6571499ab49987e", 125032322, 16777217),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "b3db40dee64ffae4694809a7c82f18c6533b054980bdf184c6571499ab49987e", 243422376, 7340032),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "610b576b84b8d2036b4d4828857924c1e1f76f6978f44237e2e16aaa1412a0fc", 275684975, 4259905),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "8565854188ef6a2319c55f9e2b61a422ef4ad984c4207c661413ee5a7f9ab0c1", 125044666, 16777224),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "8565854188ef6a2319c55f9e2b61a422ef4ad984c4207c661413ee5a7f9ab0c1", 243437853, 7340033),
 }
 
 
