@@ -459,6 +459,13 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     if (nf == 4 && mt == 3) mt = 4;  // four column tiles per wave are built for 64- and 128-row tiles only
     gz = (M + 32 * mt - 1) / (32 * mt);  // mt may have changed above
     int gx = (tiles + 4 * nf - 1) / (4 * nf);
+    // an unsliced projection whose 64-row tiles give a few workgroups more than two per CU takes 96-row tiles if those
+    // fit (gate/up at 289..320 rows: 560 workgroups 190 us, 448 workgroups 167 us)
+    if (!tn.linear_mt && !part && mt == 2 && prologue == PRO_NONE && nf <= 2 && gx * gz > 2 * kNumCU && gx * gz <= 3 * kNumCU &&
+        gx * ((M + 95) / 96) <= 2 * kNumCU) {
+        mt = 3;
+        gz = (M + 95) / 96;
+    }
     // A projection that cannot slice K (no workspace) runs one workgroup per CU; a ring of 8 k-steps then keeps twice
     // the weight bytes in flight per wave, which measured 9 % faster on the gate/up shape at 64 rows.
     const bool ks8 = (mt == 2 || (mt == 3 && nf == 1 && prologue == PRO_NONE)) && nf <= 2 && prologue != PRO_PACKED &&
@@ -469,7 +476,14 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     // never a few workgroups more than one per CU: the CUs that get a second one take twice as long (264 workgroups
     // of the one-per-CU shape took 141 us where 240 take 100; the QKV projection at 64 rows 20.7 us with 288
     // workgroups, 16.2 us with 240)
-    if (!tn.linear_ksplit && gx * gz * ksplit > kNumCU && gx * gz <= kNumCU) ksplit = kNumCU / (gx * gz);
+    // (except that two slices on two workgroups per CU beat one slice on fewer workgroups than CUs, for the shapes
+    // that fit two on a CU: 384 workgroups 65 us, 192 workgroups 73 us; but 192 with two slices 40 us, 288 with
+    // three 46 us)
+    const bool one_per_cu = mt * nf > 8 || (mt == 4 && prologue != PRO_NONE);
+    if (!tn.linear_ksplit && gx * gz * ksplit > kNumCU && gx * gz <= kNumCU) {
+        const int fl = kNumCU / (gx * gz);
+        if (one_per_cu || fl >= 2) ksplit = fl;
+    }
     if (ksplit > chunks / 2) ksplit = chunks / 2;
     if (ksplit > max_split) ksplit = max_split;
     if (!part) ksplit = 1;
