@@ -194,6 +194,7 @@ def main():
         roof["traffic"] = measured_traffic(a.workload, dom)
 
     step_bytes = W.algorithmic_bytes(m, wl.lens, batch)
+    step_flops = W.algorithmic_flops(m, wl.lens, batch)
     out = dict(metric="decode_tokens_per_s", value=round(tokens_per_s, 1), unit="tokens/s", n_gpus=1, steps=a.steps,
                warmup=a.warmup, ms_per_step=round(sec * 1e3, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="bf16", data="synthetic",
@@ -202,6 +203,9 @@ def main():
                roofline=roof,
                step=dict(algorithmic_GB=round(step_bytes / 1e9, 3), hbm_floor_ms=round(step_bytes / HBM_PEAK_GBS / 1e6, 3),
                          frac_of_hbm_floor=round(step_bytes / HBM_PEAK_GBS / 1e9 / sec, 4),
+                         algorithmic_TFLOP=round(step_flops / 1e12, 3),
+                         mfma_floor_ms=round(step_flops / MFMA_BF16_PEAK_TFLOPS / 1e9, 3),
+                         frac_of_roofline=round(max(step_bytes / HBM_PEAK_GBS / 1e9, step_flops / MFMA_BF16_PEAK_TFLOPS / 1e12) / sec, 4),
                          sum_of_kernel_ms=round(step_kernel_ms, 3)),
                kernels=kernels)
 
@@ -211,7 +215,10 @@ def main():
                                      iters=max(3, min(a.steps, 10)), logits=logits)
         for p in pts:
             by = W.algorithmic_bytes(m, wl.lens, p["batch"])
+            fl = W.algorithmic_flops(m, wl.lens, p["batch"])
             p["frac_of_hbm_floor"] = round(by / HBM_PEAK_GBS / 1e6 / p["lat_ms_median"], 4)
+            # the step's roofline: the larger of its HBM time and its matrix-core time at the published peaks
+            p["frac_of_roofline"] = round(max(by / HBM_PEAK_GBS / 1e6, fl / MFMA_BF16_PEAK_TFLOPS / 1e9) / p["lat_ms_median"], 4)
             p["context_tokens"] = int(wl.lens[:p["batch"]].astype(np.int64).sum()) + p["batch"]
             log("batch %4d: %.3f ms  %.0f tok/s  (%.1f%% of HBM floor)" % (
                 p["batch"], p["lat_ms_median"], p["tokens_per_s"], 100 * p["frac_of_hbm_floor"]))

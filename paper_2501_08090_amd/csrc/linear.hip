@@ -439,11 +439,34 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     int mt = tn.linear_mt ? tn.linear_mt : (big ? 4 : (M > 64 && pad96 <= pad64 ? 3 : (M > 32 ? 2 : 1)));
     int tiles = L.Npad / 32;
     int gz = (M + 32 * mt - 1) / (32 * mt);
-    // Column tiles per wave of a projection that cannot slice K: two as soon as that still gives about one workgroup
-    // per CU (224 for a 57344-wide gate/up: 190 against 260 us at 65 rows with hidden size 8192), else one
-    int nf = tn.linear_nf ? tn.linear_nf
-                          : (big && tiles >= 256 ? 4
-                             : ((!part && ((tiles + 7) / 8) * gz < 200) || tiles < 64 || (part && M <= 64) ? 1 : 2));
+    // Column tiles per wave.  A projection that cannot slice K takes the smallest count that fits the grid into one
+    // round of the chip (224 workgroups for a 57344-wide gate/up with two tiles: 190 against 260 us at 65 rows; 251 for
+    // the LM head with four: 169 against 192 us at 64 rows), two if none does.  A sliced one takes one tile up to 64
+    // rows and two above, and more where the K-slices that fill the grid still hold twelve chunks or more (hidden
+    // size 8192: QKV 34 against 39 us at 64 rows with two tiles, 50 against 56 us at 128 rows with four): wider
+    // workgroups re-read the activations less often, but short slices are mostly ramp.
+    int nf;
+    if (tn.linear_nf) nf = tn.linear_nf;
+    else if (big && tiles >= 256) nf = 4;
+    else if (tiles < 64) nf = 1;
+    else if (!part) {
+        const int max_nf = mt == 3 ? 2 : 4;
+        nf = 1;
+        while (nf < max_nf && ((tiles + 4 * nf - 1) / (4 * nf)) * gz > kNumCU) nf *= 2;
+        if (((tiles + 4 * nf - 1) / (4 * nf)) * gz > kNumCU) nf = 2;
+    } else {
+        nf = M <= 64 ? 1 : 2;
+        const int max_nf = mt == 3 || prologue != PRO_NONE ? 2 : 4;
+        const int chunks64 = (L.K + 63) / 64;
+        for (int c = max_nf; c > nf; c /= 2) {
+            const int g = ((tiles + 4 * c - 1) / (4 * c)) * gz;
+            const int ks = g >= kNumCU ? 1 : (kNumCU / g < max_split ? kNumCU / g : max_split);
+            if (chunks64 / ks >= 12) {
+                nf = c;
+                break;
+            }
+        }
+    }
     // (MT=2, NF=1, KS=4, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
     // (the KS=8 build of it compiles but measured slower than two tiles per wave: 45 vs 36 us at 64 rows)
     if (prologue == PRO_SWIGLU) nf = 2;

@@ -141,3 +141,10 @@ def algorithmic_bytes(m, lens, batch):
     ctx = int(np.asarray(lens[:batch], np.int64).sum()) + batch
     kappa = kv_bytes_per_token(m)
     return 2 * streamed_params(m) + kappa * ctx + kappa * batch + 4 * batch * m["vocab"]
+
+
+def algorithmic_flops(m, lens, batch):
+    """Flops one step must do: two per streamed weight and request, four per query head, head dimension, layer and
+    attended token (scores and weighted sum)."""
+    ctx = int(np.asarray(lens[:batch], np.int64).sum()) + batch
+    return 2 * batch * streamed_params(m) + 4 * m["n_q_heads"] * m["head_dim"] * m["n_layers"] * ctx
