@@ -26,9 +26,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "610b576b84b8d2036b4d4828857924c1e1f76f6978f44237e2e16aaa1412a0fc", 275693815, 4259910),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "a7a87b9d4b68a5a8e87fab8605ffbf78ca38f31062271a3429edeb2df7d5732d", 125044760, 16777246),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "a7a87b9d4b68a5a8e87fab8605ffbf78ca38f31062271a3429edeb2df7d5732d", 243438033, 7340032),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "610b576b84b8d2036b4d4828857924c1e1f76f6978f44237e2e16aaa1412a0fc", 275677837, 4259909),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "62b703260792182421d6b4af86cd56400c658f67d70fdf32d953bb316f213c9a", 125044549, 16777221),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "62b703260792182421d6b4af86cd56400c658f67d70fdf32d953bb316f213c9a", 243437622, 7340032),
 }
 
 
