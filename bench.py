@@ -18,6 +18,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+DEFAULT_WORKLOAD = "llama8b-b64-lognormal800"
+CURVE_WORKLOAD = "llama8b-mixed-sweep512"   # same model shape: the curve the local autoscaler tunes
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
@@ -109,7 +111,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama8b-b64-lognormal800")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--sweep", action="store_true", help="also time the batch-size sweep (prefixes of the batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=32)
@@ -121,6 +123,9 @@ def main():
                     help="also run one plain 1 GiB device copy (known bytes) so that rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE "
                          "readings of the kernels can be scaled by what the same counter reads for it")
     ap.add_argument("--batch", type=int, default=0, help="time a prefix of the workload's batch instead of all of it")
+    ap.add_argument("--no-curve", action="store_true",
+                    help="default workload only: skip the latency/throughput curve over batch sizes 1..512 of the mixed "
+                         "population that is otherwise measured after the step (kernel profiles of the step use this)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
@@ -139,8 +144,11 @@ def main():
     batch = min(a.batch, full_batch) if a.batch > 0 else full_batch
     sample = list(range(min(a.cpu_sample, batch))) if not a.no_cpu_baseline else []
     t0 = time.time()
+    curve = a.workload == DEFAULT_WORKLOAD and not a.no_curve and batch == full_batch
+    cm, _, cbatch, _ = W.WORKLOADS[CURVE_WORKLOAD]
     wl = W.build(a.workload, seed=0, host_seqs=sample, host_weights=bool(sample), log=log,
-                 max_batch=full_batch * max(1, a.q_len))
+                 max_batch=max(full_batch * max(1, a.q_len), cbatch if curve else 0),
+                 max_blocks_per_seq=(8192 + 16) // 16 + 1 if curve else None)
     if batch != full_batch:
         wl.context_tokens = int(wl.lens[:batch].astype(np.int64).sum()) + batch
     log("workload %s built in %.1f s: batch %d, %d context tokens, pool %d pages" % (
@@ -293,6 +301,27 @@ def main():
             out["parity_sample"]["argmax_agreement"]))
     else:
         out["cpu_baseline"] = None
+    if curve:
+        # Per-step latency and tokens/s over batch sizes 1..512 of the mixed population (Local Autoscaler: the curve
+        # its batch-size updates walk), on the same model: the default workload's cache is released first.
+        model = wl.model
+        del logits
+        wl.pool.close()
+        del wl
+        torch.cuda.empty_cache()
+        t0 = time.time()
+        cw = W.build(CURVE_WORKLOAD, seed=0, model=model)
+        log("curve workload %s built in %.1f s: %d requests, %d context tokens" % (CURVE_WORKLOAD, time.time() - t0, cbatch, cw.context_tokens))
+        clog = torch.empty((cbatch, cm["vocab"]), dtype=torch.float32, device="cuda")
+        sizes = [b for b in W.SWEEP_BATCHES if b <= cbatch]
+        pts = B.step_latency_profile(model, cw.pool, cw.block_table, cw.seq_lens, cw.tokens, sizes, warmup=2, iters=5, logits=clog)
+        for p in pts:
+            by, fl = W.algorithmic_bytes(cm, cw.lens, p["batch"]), W.algorithmic_flops(cm, cw.lens, p["batch"])
+            p["context_tokens"] = int(cw.lens[:p["batch"]].astype(np.int64).sum()) + p["batch"]
+            p["frac_of_roofline"] = round(max(by / HBM_PEAK_GBS / 1e6, fl / MFMA_BF16_PEAK_TFLOPS / 1e9) / p["lat_ms_median"], 4)
+            log("curve: batch %4d: %.3f ms  %.0f tok/s  (%.1f%% of the step's roofline)" % (
+                p["batch"], p["lat_ms_median"], p["tokens_per_s"], 100 * p["frac_of_roofline"]))
+        out["curve"] = dict(workload=CURVE_WORKLOAD, points=pts)
     print(json.dumps(out), flush=True)
 
 

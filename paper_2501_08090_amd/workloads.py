@@ -80,11 +80,12 @@ def build_model(m, seed=0, max_batch=1, max_blocks_per_seq=1, host_weights=False
 
 
 def build(name, seed=0, host_seqs=(), host_weights=False, max_batch=None, log=None, gain_jitter=0.0, model=None,
-          w_host=None, pool_memory=None):
+          w_host=None, pool_memory=None, max_blocks_per_seq=None):
     """Returns a Workload with .model .pool .block_table .seq_lens .tokens (GPU) and .lens .bt .tok (numpy).
     host_weights / host_seqs additionally fill .w_host (numpy storage arrays) and .kv_host[l] = (K, V) rows of
     the listed requests, concatenated in the order given.  An existing model of the same shape (created with a
-    large enough max_batch and max_blocks_per_seq) can be passed in to skip the weight generation."""
+    large enough max_batch and max_blocks_per_seq) can be passed in to skip the weight generation; max_batch and
+    max_blocks_per_seq size a new model for more than this workload needs, so that it can serve another one later."""
     m, kind, batch, pool_factor = WORKLOADS[name]
     m = dict(m)
     dev = "cuda"
@@ -92,7 +93,7 @@ def build(name, seed=0, host_seqs=(), host_weights=False, max_batch=None, log=No
     wl = Workload()
     wl.name, wl.m, wl.batch = name, m, batch
     wl.lens = I.population(kind, batch, seed)
-    mb = model.cfg.max_blocks_per_seq if model is not None else None
+    mb = model.cfg.max_blocks_per_seq if model is not None else max_blocks_per_seq  # None: as wide as the longest request
     wl.bt, wl.num_blocks = I.make_block_table(wl.lens, seed=seed, pool_factor=pool_factor, max_blocks=mb)
     wl.tok = I.token_ids(batch, m["vocab"], seed)
     wl.block_table = torch.from_numpy(wl.bt).to(dev)
