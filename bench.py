@@ -28,9 +28,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "610b576b84b8d2036b4d4828857924c1e1f76f6978f44237e2e16aaa1412a0fc", 275687316, 4259904),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "62b703260792182421d6b4af86cd56400c658f67d70fdf32d953bb316f213c9a", 125044594, 16777238),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "62b703260792182421d6b4af86cd56400c658f67d70fdf32d953bb316f213c9a", 243437715, 7340033),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "9ea43d6ce8f3b5dec18572d9db92b9d78c49fc1f9cf2fa199c8deccfc2654ece", 275762673, 4259900),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "62b703260792182421d6b4af86cd56400c658f67d70fdf32d953bb316f213c9a", 125044594, 16777228),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "62b703260792182421d6b4af86cd56400c658f67d70fdf32d953bb316f213c9a", 243437715, 7340032),
 }
 
 

@@ -325,7 +325,7 @@ static int32_t step_rows(chiron_model* m, chiron_kvpool* p, const int32_t* block
     int ks_res = 0, ks_qkv = 1;  // K-slices waiting in m->part for the residual stream / of the QKV projection
     STEP(CHIRON_K_OTHER, launch_embed(m->embed, tokens, B, H, m->h, st));
     STEP(CHIRON_K_OTHER, launch_rope_table(seq_lens, B, d, c.rope_base, m->cos_t, m->sin_t, st));
-    STEP(CHIRON_K_OTHER, launch_attn_plan(m->aws, req_lens, ash, n_req, c.n_kv_heads, st));
+    STEP(CHIRON_K_OTHER, launch_attn_plan(m->aws, req_lens, req_bt, mb, ash, n_req, c.n_kv_heads, st));
     for (int l = 0; l < c.n_layers; ++l) {
         // h += (slices of the previous down projection); x = norm(h)
         STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->attn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
@@ -607,7 +607,7 @@ int32_t chiron_op_paged_attention(chiron_model* m, const chiron_kvpool* p, int32
     hipStream_t st = (hipStream_t)stream;
     const int qn = m->cfg.n_q_heads * m->cfg.head_dim;
     const AttnShape sh = attn_shape(m->cfg.n_q_heads / m->cfg.n_kv_heads, 1, 0);
-    int32_t rc = launch_attn_plan(m->aws, ctx_lens, sh, batch, m->cfg.n_kv_heads, st);
+    int32_t rc = launch_attn_plan(m->aws, ctx_lens, block_table, m->cfg.max_blocks_per_seq, sh, batch, m->cfg.n_kv_heads, st);
     if (rc) return rc;
     rc = launch_attn_main(m->aws, p->d, layer, q, qn, m->cfg.n_q_heads, block_table, m->cfg.max_blocks_per_seq, ctx_lens, sh,
                           batch, st);

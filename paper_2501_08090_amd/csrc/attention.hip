@@ -26,7 +26,13 @@ namespace chiron {
 // plan buffer layout (int32): [0] n_items, [1] chunk_pages, [2..3] unused,
 // [4, 4+max_batch) first item of pass v, [.., +max_batch) number of items of pass v,
 // then item_seq[cap_items] (the pass), item_pg0[cap_items].  A pass v = request * ng + token group (AttnShape).
-int64_t attn_plan_ints(int max_batch, int cap_items) { return 4 + 2 * (int64_t)max_batch + 2 * (int64_t)cap_items; }
+// Last, 32-byte aligned, one record of 8 ints per item: {pass, first page, attended length, the ids of the item's
+// first four pages (past its end: its last page), 0}: everything a wave needs before its first tile load, in one
+// scalar load instead of a chain of four dependent ones (the block table does not differ between layers).
+__host__ __device__ inline int64_t plan_rec_offset(int max_batch, int cap_items) {
+    return (4 + 2 * (int64_t)max_batch + 2 * (int64_t)cap_items + 7) / 8 * 8;
+}
+int64_t attn_plan_ints(int max_batch, int cap_items) { return plan_rec_offset(max_batch, cap_items) + 8 * (int64_t)cap_items; }
 
 AttnShape attn_shape(int G, int q_len, int len_bias) {
     AttnShape sh;
@@ -47,7 +53,8 @@ constexpr int kPlanThreads = 1024;
 
 __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __restrict__ plan, int max_batch, int cap_items,
                                                                  const int32_t* __restrict__ seq_lens, AttnShape sh,
-                                                                 int batch, int n_kv, int slots, int target_waves, int force_cp, int item_limit) {
+                                                                 int batch, int n_kv, int slots, int target_waves, int force_cp, int item_limit,
+                                                                 const int32_t* __restrict__ bt, int max_blocks) {
     batch *= sh.ng;  // passes
     __shared__ int scan[kPlanThreads];
     int32_t* seq_item0 = plan + 4;
@@ -120,9 +127,18 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
         int nch = (np + cp - 1) / cp;
         seq_item0[i] = off;
         seq_nch[i] = nch;
+        const int len = pass_len(seq_lens, sh, i);
+        const int32_t* btrow = bt + (size_t)(i / sh.ng) * max_blocks;
         for (int ch = 0; ch < nch; ++ch) {
             item_seq[off + ch] = i;
             item_pg0[off + ch] = ch * cp;
+            int32_t* rec = plan + plan_rec_offset(max_batch, cap_items) + 8 * (int64_t)(off + ch);
+            const int pg1 = min(ch * cp + cp, np);
+            rec[0] = i;
+            rec[1] = ch * cp;
+            rec[2] = len;
+            for (int u = 0; u < 4; ++u) rec[3 + u] = btrow[min(ch * cp + u, pg1 - 1)];
+            rec[7] = 0;
         }
         off += nch;
     }
@@ -132,7 +148,8 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     }
 }
 
-int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const AttnShape& sh, int batch, int n_kv, hipStream_t st) {
+int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const int32_t* bt, int max_blocks, const AttnShape& sh,
+                         int batch, int n_kv, hipStream_t st) {
     const Tuning& t = tuning();
     if ((int64_t)batch * sh.ng > ws.max_batch) return fail(CHIRON_ERR_BATCH_TOO_LARGE, "attention: %d requests x %d token groups exceed the workspace", batch, sh.ng);
     const int slots = 4 * (t.attn_grid > 0 ? t.attn_grid : kNumCU * 2);  // waves of the persistent attention grid
@@ -140,7 +157,8 @@ int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const
         return fail(CHIRON_ERR_BATCH_TOO_LARGE, "attention: %d passes do not fit a work list of %d items", batch * sh.ng, ws.cap_items / sh.tg);
     launch(attn_plan_kernel, dim3(1), dim3(kPlanThreads), st, ws.plan, ws.max_batch, ws.cap_items, seq_lens, sh, batch, n_kv, slots,
                                                   t.attn_target_waves > 0 ? t.attn_target_waves : 4 * slots, t.attn_chunk_pages,
-                                                  ws.cap_items / sh.tg);  // a partial result holds tg tokens' heads
+                                                  ws.cap_items / sh.tg,  // a partial result holds tg tokens' heads
+                                                  bt, max_blocks);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -164,24 +182,32 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
     const int n_kv = p.n_kv;
     const int n_work = plan[0] * n_kv;
     const int cp = plan[1];
-    const int32_t* item_seq = plan + 4 + 2 * max_batch;
-    const int32_t* item_pg0 = item_seq + cap_items;
     const int head = lane & 15, lg = lane >> 4;
     const int pcols = MULTI ? G * sh.tg : G;         // columns of a partial result
     const int tq = MULTI ? head / G : 0, hq = MULTI ? head % G : head;
     const size_t tile_elems = (size_t)16 * D;
 
-    // item metadata (request, first page, length) is fetched one item ahead
+    // item metadata (pass, first page, length, first page ids) comes in one record, fetched one item ahead.  The first
+    // record is read without waiting for the item count (any record of the list is readable memory; a wave past the
+    // end of the list discards it).
+    const int32_t* recs = plan + plan_rec_offset(max_batch, cap_items);
     int w = blockIdx.x * 4 + wave;
-    int v_nx = 0, pg0_nx = 0, len_nx = 0;
-    if (w < n_work) {
-        v_nx = __builtin_amdgcn_readfirstlane(item_seq[w / n_kv]);
-        pg0_nx = __builtin_amdgcn_readfirstlane(item_pg0[w / n_kv]);
-        len_nx = __builtin_amdgcn_readfirstlane(pass_len(seq_lens, sh, v_nx));
-    }
+    int v_nx, pg0_nx, len_nx, b0_nx, b1_nx, b2_nx, b3_nx;
+    auto fetch_rec = [&](int item) {
+        const int32_t* r = recs + 8 * (size_t)min(item, cap_items - 1);
+        v_nx = __builtin_amdgcn_readfirstlane(r[0]);
+        pg0_nx = __builtin_amdgcn_readfirstlane(r[1]);
+        len_nx = __builtin_amdgcn_readfirstlane(r[2]);
+        b0_nx = __builtin_amdgcn_readfirstlane(r[3]);
+        b1_nx = __builtin_amdgcn_readfirstlane(r[4]);
+        b2_nx = __builtin_amdgcn_readfirstlane(r[5]);
+        b3_nx = __builtin_amdgcn_readfirstlane(r[6]);
+    };
+    fetch_rec(w / n_kv);
     for (; w < n_work; w += n_waves) {
         const int it = w / n_kv, c = w - it * n_kv;
         const int pg0 = pg0_nx, len = len_nx;
+        const int first_ids[4] = {b0_nx, b1_nx, b2_nx, b3_nx};
         const int i = MULTI ? v_nx / sh.ng : v_nx, g = MULTI ? v_nx - i * sh.ng : 0;
         const int tv = MULTI ? min(sh.tg, sh.q_len - g * sh.tg) : 1;  // tokens of this pass
         const int cols = G * tv;                                       // live operand columns
@@ -284,18 +310,14 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
 
         // The steady loop has no divergent branch and a fixed order of loads (next stage's tiles first, then
         // this stage's arithmetic), so exactly one stage of loads stays in flight behind the one in use.
-        fetch_ids(pg0);
+        static_assert(NPG == 2, "the item record carries the ids of two stages of two pages");
+        blk_next[0] = first_ids[0];
+        blk_next[1] = first_ids[1];
         load_group(kc, vc);   // the first tiles are on their way before anything else of the item is touched
-        fetch_ids(pg0 + NPG);
+        blk_next[0] = first_ids[2];
+        blk_next[1] = first_ids[3];
         __builtin_amdgcn_sched_barrier(0);
-        {
-            const int wn = w + n_waves;  // next item's metadata, needed only after this item is done
-            if (wn < n_work) {
-                v_nx = __builtin_amdgcn_readfirstlane(item_seq[wn / n_kv]);
-                pg0_nx = __builtin_amdgcn_readfirstlane(item_pg0[wn / n_kv]);
-                len_nx = __builtin_amdgcn_readfirstlane(pass_len(seq_lens, sh, v_nx));
-            }
-        }
+        fetch_rec((w + n_waves) / n_kv);  // next item's record, needed only after this item is done
         // q fragments: operand column = head, 8 consecutive dims per lane group; scaled by log2(e)/sqrt(d)
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {

@@ -157,7 +157,9 @@ struct AttnShape {
 // len_bias: what to add to seq_lens[i] for the number of positions the LAST new token attends (q_len when all new
 // tokens are appended and seq_lens counts only the older ones; 0 when seq_lens is already the attended length)
 AttnShape attn_shape(int G, int q_len, int len_bias);
-int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const AttnShape& sh, int batch, int n_kv, hipStream_t st);
+// (bt: the block table the attention launches of this plan will use; the plan copies each item's first page ids)
+int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const int32_t* bt, int max_blocks, const AttnShape& sh,
+                         int batch, int n_kv, hipStream_t st);
 int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
                          const int32_t* bt, int max_blocks, const int32_t* seq_lens, const AttnShape& sh, int batch,
                          hipStream_t st);
