@@ -161,6 +161,30 @@ def test_swiglu_linear(M, N, K):
     lin.close()
 
 
+def test_linear_over_seeded_random_shapes():
+    """The launch shape (rows per tile, column tiles per wave, K-slices, pre-split input) is chosen from M, N and K by
+    several rules: 48 seeded random shapes, widths from a few columns to more than two workgroups per CU and rows
+    across every tile boundary, each against the oracle, plain and with the SwiGLU prologue."""
+    rng = np.random.default_rng(2024)
+    for case in range(48):
+        M = int(rng.integers(1, 700))
+        N = int(rng.choice([rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 40000)]))
+        K = 16 * int(rng.integers(1, 1 + (64 if N < 3000 else 16)))
+        x = rng.standard_normal((M, K)).astype(np.float32)
+        W = I.normal((N, K), 0.05, 9, "wr", case)
+        print("random linear", case, M, N, K, flush=True)
+        lin = B().Linear(W.cuda())
+        want = orc.linear(x, I.to_numpy_storage(W))
+        got = lin(torch.from_numpy(x).cuda()).cpu().numpy()
+        assert rel_err(got, want) <= KERNEL_TOL, (M, N, K)
+        if case % 3 == 0:
+            gu = (rng.standard_normal((M, 2 * K)) * 2).astype(np.float32)
+            got = lin.swiglu(torch.from_numpy(gu).cuda()).cpu().numpy()
+            want = orc.linear(orc.swiglu(gu[:, :K], gu[:, K:]), I.to_numpy_storage(W))
+            assert rel_err(got, want) <= KERNEL_TOL, (M, N, K, "swiglu")
+        lin.close()
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 512, 256), (300, 1000, 688), (513, 2080, 1040), (97, 96, 64), (640, 4096, 512)])
 def test_linear_large_batch_kernel(M, N, K):
     """the large-batch path (activations pre-split into tiled bf16 terms, copied straight into LDS), forced at any M"""
