@@ -254,6 +254,35 @@ def test_paged_attention(d, nq, nkv, lens):
         assert np.abs(got - want).max() <= KERNEL_TOL * max(1.0, np.abs(want).max())
 
 
+@pytest.mark.parametrize("grid,chunk", [(4, 0), (4, 3), (2, 1), (0, 5)])
+def test_paged_attention_work_list_over_several_rounds(grid, chunk):
+    """A small persistent grid (grid workgroups = 4*grid wave slots) makes every wave walk several items of the work
+    list, whose records are fetched one item ahead; forced chunk sizes give items of 1, 3 or 5 pages with ragged
+    ends.  24 requests of 1..1500 cached tokens, 4 query heads per KV head."""
+    d, nq, nkv = 128, 8, 2
+    rng = np.random.default_rng(41)
+    lens = rng.integers(1, 1500, size=24).astype(np.int32)
+    lens[:4] = [1, 16, 17, 1499]
+    m = dict(I.TINY, n_layers=1, head_dim=d, n_q_heads=nq, n_kv_heads=nkv, hidden=256)
+    c = make_case(m=m, seed=17, storage="bf16", seq_lens=lens, poison_unused=True)
+    g = gpu_setup(c, poison=True)
+    opool = fresh_pool(c)
+    q = (rng.standard_normal((len(lens), nq * d)) * 1.3).astype(np.float32)
+    b = B()
+    b.set_tuning("attn_grid", grid)
+    b.set_tuning("attn_chunk_pages", chunk)
+    try:
+        print("attention grid", grid, "chunk", chunk, flush=True)
+        got = b.op_paged_attention(g.model, g.pool, 0, torch.from_numpy(q).cuda(), g.block_table, g.seq_lens).cpu().numpy()
+    finally:
+        b.set_tuning("attn_grid", 0)
+        b.set_tuning("attn_chunk_pages", 0)
+    want = np.stack([orc.paged_attention(opool, 0, c.block_table[i], int(lens[i]), q[i].reshape(nq, d)).reshape(-1)
+                     for i in range(len(lens))])
+    assert np.all(np.isfinite(got))
+    assert np.abs(got - want).max() <= KERNEL_TOL * max(1.0, np.abs(want).max())
+
+
 # ---- the whole step ---------------------------------------------------------------------------------
 
 def run_both(c, g=None, poison=False):
