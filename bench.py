@@ -304,13 +304,15 @@ def main():
     if curve:
         # Per-step latency and tokens/s over batch sizes 1..512 of the mixed population (Local Autoscaler: the curve
         # its batch-size updates walk), on the same model: the default workload's cache is released first.
-        model = wl.model
+        model, wl_w_host = wl.model, wl.w_host
         del logits
         wl.pool.close()
         del wl
         torch.cuda.empty_cache()
         t0 = time.time()
-        cw = W.build(CURVE_WORKLOAD, seed=0, model=model)
+        w_host = wl_w_host
+        oracle_sizes = [b for b in (1, 8) if w_host is not None]   # 64 takes ~20 s more: left to `--workload ... --batch 64`
+        cw = W.build(CURVE_WORKLOAD, seed=0, model=model, host_seqs=list(range(max(oracle_sizes))) if oracle_sizes else ())
         log("curve workload %s built in %.1f s: %d requests, %d context tokens" % (CURVE_WORKLOAD, time.time() - t0, cbatch, cw.context_tokens))
         clog = torch.empty((cbatch, cm["vocab"]), dtype=torch.float32, device="cuda")
         sizes = [b for b in W.SWEEP_BATCHES if b <= cbatch]
@@ -322,6 +324,19 @@ def main():
             log("curve: batch %4d: %.3f ms  %.0f tok/s  (%.1f%% of the step's roofline)" % (
                 p["batch"], p["lat_ms_median"], p["tokens_per_s"], 100 * p["frac_of_roofline"]))
         out["curve"] = dict(workload=CURVE_WORKLOAD, points=pts)
+        if oracle_sizes:
+            # the oracle beside the curve's smallest batch sizes, on the host cores
+            sys.path.insert(0, os.path.join(ROOT, "oracle"))
+            import chiron_oracle as orc
+            import sample_step
+            orows = []
+            for b in oracle_sizes:
+                n = int(cw.lens[:b].astype(np.int64).sum())
+                _, _, _, dt = sample_step.run(cm, w_host, [(k[:n], v[:n]) for k, v in cw.kv_host], cw.lens[:b], cw.tok[:b])
+                orows.append(dict(batch=b, seconds=round(dt, 3), tokens_per_s=round(b / dt, 3), cores=orc.num_threads()))
+                log("curve: oracle at batch %d: %.2f s = %.2f tokens/s" % (b, dt, b / dt))
+            out["curve"]["oracle"] = orows
+            out["curve"]["oracle_skipped"] = [b for b in sizes if b not in oracle_sizes]
     print(json.dumps(out), flush=True)
 
 
