@@ -180,8 +180,18 @@ class KVPool:
             pass
 
 
+def _check_table(model, block_table, batch):
+    """The library indexes the block table with the model's max_blocks_per_seq as row stride."""
+    if block_table.dim() != 2 or block_table.shape[1] != model.cfg.max_blocks_per_seq:
+        raise ValueError("block_table must be [rows, %d] (the model's max_blocks_per_seq), got %s" % (
+            model.cfg.max_blocks_per_seq, tuple(block_table.shape)))
+    if block_table.shape[0] < batch:
+        raise ValueError("block_table has %d rows for a batch of %d" % (block_table.shape[0], batch))
+
+
 def decode_step(model, pool, block_table, seq_lens, tokens, logits=None, batch=None):
     B = seq_lens.numel() if batch is None else int(batch)
+    _check_table(model, block_table, B)
     if logits is None:
         logits = torch.empty((B, model.cfg.vocab), dtype=torch.float32, device="cuda")
     _check(load().chiron_decode_step(model._h, pool._h, _ptr(block_table, torch.int32), _ptr(seq_lens, torch.int32),
@@ -192,6 +202,7 @@ def decode_step(model, pool, block_table, seq_lens, tokens, logits=None, batch=N
 def decode_step_multi(model, pool, block_table, seq_lens, tokens, logits=None):
     """tokens [batch, q_len] int32 -> logits [batch, q_len, vocab]"""
     B, T = tokens.shape
+    _check_table(model, block_table, B)
     if logits is None:
         logits = torch.empty((B, T, model.cfg.vocab), dtype=torch.float32, device="cuda")
     _check(load().chiron_decode_step_multi(model._h, pool._h, _ptr(block_table, torch.int32), _ptr(seq_lens, torch.int32),
@@ -203,6 +214,7 @@ def decode_step_multi(model, pool, block_table, seq_lens, tokens, logits=None):
 def validate_step_inputs(model, pool, block_table, seq_lens, tokens, batch=None):
     """tokens [batch] or, for the multi-token step, [batch, q_len]"""
     B = seq_lens.numel() if batch is None else int(batch)
+    _check_table(model, block_table, B)
     if tokens.dim() == 2:
         _check(load().chiron_validate_step_inputs_multi(model._h, pool._h, _ptr(block_table, torch.int32), _ptr(seq_lens, torch.int32),
                                                         _ptr(tokens, torch.int32), C.c_int32(B), C.c_int32(tokens.shape[1]), _stream()))
@@ -231,6 +243,7 @@ def last_error():
 
 def step_latency_profile(model, pool, block_table, seq_lens, tokens, batch_sizes, warmup=2, iters=5, logits=None):
     n = len(batch_sizes)
+    _check_table(model, block_table, max(batch_sizes))
     if logits is None:
         logits = torch.empty((max(batch_sizes), model.cfg.vocab), dtype=torch.float32, device="cuda")
     bs = (C.c_int32 * n)(*batch_sizes)
@@ -328,6 +341,7 @@ def op_rope(x, pos, base):
 
 def op_paged_attention(model, pool, layer, q, block_table, ctx_lens):
     B = ctx_lens.numel()
+    _check_table(model, block_table, B)
     out = torch.empty_like(q)
     _check(load().chiron_op_paged_attention(model._h, pool._h, C.c_int32(layer), _ptr(q, torch.float32),
                                             _ptr(block_table, torch.int32), _ptr(ctx_lens, torch.int32), C.c_int32(B),

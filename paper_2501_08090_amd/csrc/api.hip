@@ -52,7 +52,11 @@ static int32_t linear_alloc(Linear& L, int N, int K) {
     const size_t bytes = (size_t)(L.Npad / 32) * L.tstride * 2;
     int32_t rc = dev_alloc((void**)&L.w, bytes);
     if (rc) return rc;
-    if (L.Npad != N || L.Kpad != K) CHIRON_HIP(hipMemset(L.w, 0, bytes));
+    if (L.Npad != N || L.Kpad != K) {
+        // the packing kernels run on the caller's stream, which need not be ordered after the null stream's memset
+        CHIRON_HIP(hipMemset(L.w, 0, bytes));
+        CHIRON_HIP(hipStreamSynchronize(nullptr));
+    }
     return CHIRON_OK;
 }
 
@@ -639,12 +643,18 @@ int32_t chiron_local_autoscale_step(double itl, double itl_slo, double tput_prev
 int32_t chiron_set_tuning(const char* key, int32_t value) {
     if (!key) return fail(CHIRON_ERR_INVALID_ARG, "key is null");
     Tuning& t = tuning();
-    struct { const char* k; int* p; } tab[] = {
-        {"linear_nf", &t.linear_nf}, {"linear_mt", &t.linear_mt}, {"linear_xcd_remap", &t.linear_xcd_remap}, {"linear_ksplit", &t.linear_ksplit},
-        {"linear_target_blocks", &t.linear_target_blocks}, {"linear_big_min_m", &t.linear_big_min_m}, {"linear_big_all", &t.linear_big_all}, {"linear_ks", &t.linear_ks}, {"attn_grid", &t.attn_grid},
-        {"attn_target_waves", &t.attn_target_waves}, {"attn_chunk_pages", &t.attn_chunk_pages}};
+    // allowed values per key: a value outside them would size a grid for a tile shape that is not built
+    struct { const char* k; int* p; int lo, hi; unsigned mask; } tab[] = {  // value in [lo, hi]; if mask: bit `value` set
+        {"linear_nf", &t.linear_nf, 0, 4, 0x17u},         {"linear_mt", &t.linear_mt, 0, 4, 0u},
+        {"linear_xcd_remap", &t.linear_xcd_remap, 0, 1, 0u}, {"linear_ksplit", &t.linear_ksplit, 0, 16, 0u},
+        {"linear_target_blocks", &t.linear_target_blocks, 1, 1 << 20, 0u},
+        {"linear_big_min_m", &t.linear_big_min_m, -1, 1 << 30, 0u}, {"linear_big_all", &t.linear_big_all, 0, 1, 0u},
+        {"linear_ks", &t.linear_ks, 0, 8, 0x111u},        {"attn_grid", &t.attn_grid, 0, 1 << 16, 0u},
+        {"attn_target_waves", &t.attn_target_waves, 0, 1 << 24, 0u}, {"attn_chunk_pages", &t.attn_chunk_pages, 0, 1 << 20, 0u}};
     for (auto& e : tab)
         if (!strcmp(e.k, key)) {
+            if (value < e.lo || value > e.hi || (e.mask && !((e.mask >> value) & 1u)))
+                return fail(CHIRON_ERR_INVALID_ARG, "tuning key '%s': value %d is not allowed", key, value);
             *e.p = value;
             return CHIRON_OK;
         }

@@ -109,7 +109,6 @@ int32_t launch_embed(const uint16_t* table, const int32_t* tokens, int batch, in
 // residual stream: h += sum_s part[s] (h is rewritten), then the norm is taken.
 int32_t launch_rmsnorm(float* h, const float* part, int ks, const uint16_t* gain, int rows, int n, float eps, float* out,
                        hipStream_t st);
-int32_t launch_fill_zero(float* p, int64_t n, hipStream_t st);
 // cos/sin of pos[i]*base^(-2j/d), j < d/2, evaluated in fp64 and stored as fp32 [rows, d/2] each
 int32_t launch_rope_table(const int32_t* pos, int rows, int d, float base, float* cos_t, float* sin_t, hipStream_t st);
 // rotate x [rows, n_heads, d] (row stride ldx floats) in place with the table

@@ -102,25 +102,6 @@ int32_t launch_rmsnorm(float* h, const float* part, int ks, const uint16_t* gain
     return CHIRON_OK;
 }
 
-// ---- zero fill (used instead of memset so that it can live inside captured graphs) ---------------------
-__global__ __launch_bounds__(256) void fill_zero_kernel(float4* __restrict__ p, int64_t n4, float* tail_base, int64_t n) {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t j = i; j < n4; j += stride) p[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < n - n4 * 4) tail_base[n4 * 4 + i] = 0.f;
-}
-
-int32_t launch_fill_zero(float* p, int64_t n, hipStream_t st) {
-    if (n <= 0) return CHIRON_OK;
-    int64_t n4 = n / 4;
-    int blocks = (int)((n4 + 255) / 256);
-    if (blocks < 1) blocks = 1;
-    if (blocks > 2048) blocks = 2048;
-    launch(fill_zero_kernel, dim3(blocks), dim3(256), st, reinterpret_cast<float4*>(p), n4, p, n);
-    CHIRON_HIP(hipGetLastError());
-    return CHIRON_OK;
-}
-
 // ---- rotary table: fp64 angle and trigonometry, once per step -------------------------------------------
 __global__ void rope_table_kernel(const int32_t* __restrict__ pos, int rows, int d, float base, int pos_bias,
                                   float* __restrict__ cos_t, float* __restrict__ sin_t) {

@@ -66,6 +66,13 @@ def test_null_handles_are_invalid_arguments():
     assert lib.chiron_op_linear(z, z, 1, z, 0, z) == -1
     assert lib.chiron_set_tuning(b"no_such_knob", 1) == -1
     assert lib.chiron_set_tuning(None, 1) == -1
+    # a knob takes only the values a kernel shape exists for; a rejected value leaves the knob as it was
+    for key, bad in ((b"linear_nf", 3), (b"linear_nf", 8), (b"linear_mt", 5), (b"linear_mt", -1), (b"linear_ks", 6),
+                     (b"linear_ksplit", 17), (b"attn_grid", -1), (b"linear_xcd_remap", 2), (b"attn_chunk_pages", -2)):
+        assert lib.chiron_set_tuning(key, bad) == -1 and b"not allowed" in lib.chiron_last_error()
+    for key, ok in ((b"linear_nf", 4), (b"linear_mt", 3), (b"linear_ks", 8), (b"linear_big_min_m", -1), (b"attn_grid", 7)):
+        assert lib.chiron_set_tuning(key, ok) == 0
+        assert lib.chiron_set_tuning(key, 0) == 0
     assert lib.chiron_model_destroy(z) == 0 and lib.chiron_kv_pool_destroy(z) == 0 and lib.chiron_linear_destroy(z) == 0
 
 

@@ -76,3 +76,54 @@ def test_library_rejects_bad_arguments():
     assert lib.chiron_local_autoscale_step(d(0.1), d(0.2), d(0), d(1), d(0.5), 0, C.byref(mb), None) == -1
     assert lib.chiron_local_autoscale_step(d(0.1), d(0.2), d(0), d(1), d(0.5), 64, None, None) == -1
     assert mb.value == 8
+
+
+# ---- the closed loop on fixed curves (deterministic; the measured curve is walked in the GPU tests) --------------
+
+def _loop(itl_of, slo, policy, ticks=80, limit=512):
+    """Alg. 1 ticked on a latency curve itl_of(batch) in seconds; throughput = batch / ITL.  policy 'as-printed':
+    the previous tick's throughput always enters TBP; 'reset-after-no-growth': a tick that did not scale up leaves
+    no comparable previous throughput (the next tick passes none)."""
+    mbs, tput_prev, traj = 1, 0.0, []
+    for _ in range(ticks):
+        itl = itl_of(mbs)
+        tput = mbs / itl
+        new, lb = orc.autoscale_step(itl, slo, tput_prev, tput, 0.5, limit, mbs)
+        traj.append((mbs, lb, new))
+        tput_prev = tput if (policy == "as-printed" or new > mbs) else 0.0
+        mbs = new
+    return traj
+
+
+def _affine_with_step(b):
+    # the shape of a measured decode curve: a weight-streaming floor, a per-request slope, a step where the
+    # projections need the next row tile
+    return (3.5 + 0.06 * b + (1.0 if b > 64 else 0.0)) * 1e-3
+
+
+def test_closed_loop_settles_under_the_slo_on_a_fixed_curve():
+    slo = _affine_with_step(128)
+    traj = _loop(_affine_with_step, slo, "reset-after-no-growth")
+    sizes = [b for b, _, _ in traj]
+    # climbs monotonically (no observation ever reaches backpressure one on a noise-free curve below the SLO) ...
+    assert all(n >= b for b, _, n in traj)
+    # ... and settles at the largest batch size whose latency is still under the SLO
+    assert sizes[-1] == sizes[-10] and 120 <= sizes[-1] <= 128
+    assert _affine_with_step(sizes[-1]) <= slo < _affine_with_step(sizes[-1] + 2)
+    # a tighter SLO settles lower, a looser one higher
+    lo = _loop(_affine_with_step, _affine_with_step(32), "reset-after-no-growth")[-1][0]
+    hi = _loop(_affine_with_step, _affine_with_step(400), "reset-after-no-growth", ticks=200)[-1][0]
+    assert lo <= 32 < sizes[-1] < hi <= 400
+
+
+def test_closed_loop_as_printed_collapses_once_the_batch_size_repeats():
+    """With the previous throughput always kept, the first tick whose update rounds to the same batch size is followed
+    by TBP = 1 exactly (same batch, same throughput): the batch halves, the lower throughput after the halving reads
+    as TBP > 1 and halves again, down to one request, where TBP = 1 keeps it.  This is why the closed loop here
+    forgets the previous throughput after a tick that did not scale up."""
+    slo = _affine_with_step(128)
+    traj = _loop(_affine_with_step, slo, "as-printed")
+    sizes = [b for b, _, _ in traj]
+    first_repeat = next(i for i, (b, _, n) in enumerate(traj) if n == b)
+    assert traj[first_repeat + 1][1] == 1.0 and traj[first_repeat + 1][2] < traj[first_repeat + 1][0]
+    assert sizes[-1] == 1 and max(sizes) < 32

@@ -1,7 +1,7 @@
 """Full-size parity: the 8B-shaped decoder in the launch configuration the benchmark times
 (batch 64, lognormal contexts), plus the batch-512 mixed population and the 32k-context batch,
 checked on sampled requests that the CPU oracle computes one by one, and by properties that hold
-for every row.  (The 70B-shaped case lives in test_gpu_full_size_70b.py so that this module's 8B
+for every row.  (The 70B-shaped case lives in test_gpu_3_full_size_70b.py so that this module's 8B
 model is released first.)  Needs a real MI355X: run with -m gpu."""
 import os
 import time
@@ -146,38 +146,34 @@ def test_8b_batch32_long_context(model8b):
 def test_local_autoscaler_closed_loop_on_the_mixed_population(model8b):
     """Alg. 1 driven by the measured curve: ITL = median step latency at the current maximum batch size,
     throughput = batch / ITL, both from chiron_step_latency_profile on prefixes of the 512-request mixed
-    population.  The SLO is set to the measured latency at batch 128, so no batch much above 128 is feasible.
-    Every update must equal the oracle's for the same observations; the trajectory must climb, meet backpressure,
-    halve, and then stay in a band below the SLO.  Where exactly it settles depends on the measured curve: the
-    throughput backpressure (previous over current throughput) stops the growth wherever throughput dips, e.g. at
-    the step from 64 to 65 requests, where the projections need a larger row tile.  (TBP approaches one whenever
-    the batch grows by a small factor, so growth proceeds in shrinking steps; a tick that did not scale up has no
-    comparable previous throughput for the next one, which passes tput_prev = 0.)"""
+    population.  The SLO is the measured latency at batch 128.  Asserted here is only what holds for any measured
+    curve: every update equals the oracle's for the same observations (exact), the batch size grows or stays when
+    the backpressure the library returned is below one and shrinks when it is at or above one, and it stays within
+    [1, limit].  Where the loop settles depends on the device's timings and is printed, not asserted (the
+    trajectory's shape is tested on fixed curves in test_autoscale.py).  Both caller policies are run: Alg. 1 as
+    printed (the previous tick's throughput always enters TBP) and the one the benchmark uses (a tick that did not
+    scale up leaves no comparable previous throughput, so the next tick passes none)."""
     B, W = _mods()
     model, w_host = model8b
     wl = W.build("llama8b-mixed-sweep512", seed=0, model=model, w_host=w_host)
     prof = lambda b: B.step_latency_profile(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, [b], warmup=1, iters=3)[0]
     slo = prof(128)["lat_ms_median"] * 1e-3
-    mbs, tput_prev, traj = 1, 0.0, []
-    for tick in range(56):
-        pt = prof(mbs)
-        itl, tput = pt["lat_ms_median"] * 1e-3, pt["tokens_per_s"]
-        new, lb = B.local_autoscale_step(itl, slo, tput_prev, tput, mbs, 512)
-        assert (new, lb) == orc.autoscale_step(itl, slo, tput_prev, tput, 0.5, 512, mbs)
-        traj.append((mbs, round(itl * 1e3, 3), round(lb, 3), new))
-        tput_prev = tput if new > mbs else 0.0
-        mbs = new
-    print("SLO %.3f ms; (batch, itl ms, backpressure, next batch):" % (slo * 1e3), traj, flush=True)
-    assert any(lb >= 1.0 for _, _, lb, _ in traj), "never met backpressure"
-    assert any(n > b for b, _, _, n in traj) and any(n < b for b, _, _, n in traj)
-    # the update rule against the observations it was given: grow below backpressure one, shrink at or above it
-    for b_, _, lb, n in traj:
-        assert (n >= b_) if lb < 1.0 else (n < b_ or b_ == 1)
-    # never far past the SLO: the latency SLO is the measured latency at 128 requests
-    assert max(b_ for b_, _, _, _ in traj) <= 160
-    assert all(itl <= slo * 1e3 * 1.15 for _, itl, _, _ in traj)
-    late = [b_ for b_, _, _, _ in traj[40:]]
-    assert min(late) >= 16 and max(late) <= 160
+    limit = 512
+    for policy in ("as-printed", "reset-after-no-growth"):
+        mbs, tput_prev, traj = 1, 0.0, []
+        for tick in range(40):
+            pt = prof(mbs)
+            itl, tput = pt["lat_ms_median"] * 1e-3, pt["tokens_per_s"]
+            assert itl > 0 and tput > 0
+            new, lb = B.local_autoscale_step(itl, slo, tput_prev, tput, mbs, limit)
+            assert (new, lb) == orc.autoscale_step(itl, slo, tput_prev, tput, 0.5, limit, mbs)
+            # the rule, on the exact backpressure the library returned (rounded only for printing below)
+            assert 1 <= new <= limit
+            assert (new >= mbs) if lb < 1.0 else (new < mbs or mbs == 1)
+            traj.append((mbs, round(itl * 1e3, 3), round(lb, 4), new))
+            tput_prev = tput if (policy == "as-printed" or new > mbs) else 0.0
+            mbs = new
+        print("policy %s, SLO %.3f ms; (batch, itl ms, backpressure, next batch):" % (policy, slo * 1e3), traj, flush=True)
     wl.pool.close()
     del wl
     torch.cuda.empty_cache()
