@@ -44,6 +44,15 @@ int32_t chiron_op_swiglu_linear(const chiron_linear *l, const float *gu, int32_t
 int32_t chiron_op_rope(float *x, int32_t rows, int32_t n_heads, int32_t d, const int32_t *pos, float base,
                        void *stream);
 
+/* chiron_op_rope for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same kernels, bit-identical result, but the cos/sin
+ * table the two kernels share lives in a fixed 1 MiB device array inside the library (one per GPU, held until the
+ * process ends) instead of a stream-ordered allocation.  The call itself allocates nothing.  Limit: rows * d <=
+ * 262144 (e.g. 2048 rows at head_dim 128); beyond it CHIRON_ERR_SHAPE and nothing is launched.  All calls on one
+ * GPU share the array: calls that overlap there (different streams or threads) race; calls on one stream do not. */
+int32_t chiron_op_rope_noalloc(float *x, int32_t rows, int32_t n_heads, int32_t d, const int32_t *pos, float base,
+                               void *stream);
+
 /* Paged GQA decode attention of one layer: for request i and query head a (KV head a / G)
  *     out[i][a] = softmax_t(q[i][a] . K_t / sqrt(d)) . V_t   over positions t < ctx_lens[i]
  * of the request's paged cache.  q, out dev fp32 [batch, n_q_heads*head_dim]; ctx_lens dev

@@ -25,7 +25,7 @@ SYMBOLS = [
     "chiron_validate_step_inputs_multi", "chiron_check_step_inputs_host_multi", "chiron_step_latency_profile",
     "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end", "chiron_local_autoscale_step",
     "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_op_swiglu_linear",
-    "chiron_op_rope", "chiron_op_paged_attention", "chiron_set_tuning",
+    "chiron_op_rope", "chiron_op_rope_noalloc", "chiron_op_paged_attention", "chiron_set_tuning",
 ]
 
 
@@ -336,6 +336,14 @@ def op_rope(x, pos, base):
     rows, nh, d = x.shape
     _check(load().chiron_op_rope(_ptr(x, torch.float32), C.c_int32(rows), C.c_int32(nh), C.c_int32(d), _ptr(pos, torch.int32),
                                  C.c_float(base), _stream()))
+    return x
+
+
+def op_rope_noalloc(x, pos, base):
+    """op_rope through the entry point that allocates nothing (fixed table inside the library)."""
+    rows, nh, d = x.shape
+    _check(load().chiron_op_rope_noalloc(_ptr(x, torch.float32), C.c_int32(rows), C.c_int32(nh), C.c_int32(d),
+                                         _ptr(pos, torch.int32), C.c_float(base), _stream()))
     return x
 
 

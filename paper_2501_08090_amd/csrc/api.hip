@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <unordered_set>
 #include <vector>
@@ -596,6 +597,51 @@ int32_t chiron_op_rope(float* x, int32_t rows, int32_t n_heads, int32_t d, const
     int32_t rc = launch_rope_table(pos, rows, d, base, tab, tab + n, st);
     if (!rc) rc = launch_rope(x, n_heads * d, n_heads, d, tab, tab + n, rows, st);
     (void)hipFreeAsync(tab, st);
+    return rc;
+}
+
+// ---- the rotary embedding for callers that cannot allocate ---------------------------------------------------
+// Same kernels as chiron_op_rope; the cos/sin table they pass between them lives in a file-scope device array
+// instead of a hipMallocAsync block.  `scratch` names the array for the device compiler only: host code never passes
+// the name to a kernel or a copy but the address that hipGetSymbolAddress reports, looked up once per device (each
+// device holds its own copy of the array at its own address).
+static constexpr size_t kRopeScratchFloats = (size_t)1 << 18;  // 1 MiB: cos and sin of rows * d/2 angles each
+static __device__ __align__(256) float scratch[kRopeScratchFloats];
+static constexpr int kMaxDevices = 64;
+static float* g_scratch_addr[kMaxDevices];  // per device, null until looked up
+static std::mutex g_scratch_mutex;
+
+static int32_t rope_scratch(float** out) {
+    int dev = -1;
+    CHIRON_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CHIRON_ERR_HIP, "rope_noalloc: device index %d is out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_addr[dev]) {
+        void* p = nullptr;
+        CHIRON_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(CHIRON_ERR_HIP, "rope_noalloc: the scratch array has no address on device %d", dev);
+        g_scratch_addr[dev] = (float*)p;
+    }
+    *out = g_scratch_addr[dev];
+    return CHIRON_OK;
+}
+
+int32_t chiron_op_rope_noalloc(float* x, int32_t rows, int32_t n_heads, int32_t d, const int32_t* pos, float base,
+                               void* stream) {
+    if (rows < 0 || n_heads < 1 || d < 2 || (d & 1)) return fail(CHIRON_ERR_INVALID_ARG, "rope: bad sizes");
+    if (rows == 0) return CHIRON_OK;
+    if (!x || !pos) return fail(CHIRON_ERR_INVALID_ARG, "rope: a pointer is null");
+    const size_t n = (size_t)rows * (d / 2);
+    if (2 * n > kRopeScratchFloats)
+        return fail(CHIRON_ERR_SHAPE, "rope_noalloc: rows*d = %zu exceeds the fixed table of %zu values (use chiron_op_rope)",
+                    2 * n, kRopeScratchFloats);
+    float* tab = nullptr;
+    int32_t rc = rope_scratch(&tab);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    // the table kernel writes every entry the rotation reads (rows * d/2 of each half): nothing to clear
+    rc = launch_rope_table(pos, rows, d, base, tab, tab + n, st);
+    if (!rc) rc = launch_rope(x, n_heads * d, n_heads, d, tab, tab + n, rows, st);
     return rc;
 }
 

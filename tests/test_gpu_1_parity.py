@@ -493,9 +493,15 @@ def test_error_paths_on_device():
     g = gpu_setup(c)
     Bd = B()
     with pytest.raises(Bd.ChironError) as e:
-        Bd.decode_step(g.model, g.pool, g.block_table, g.seq_lens, g.tokens, batch=5,
+        five = lambda t: torch.cat([t, t[:1]]).contiguous()
+        Bd.decode_step(g.model, g.pool, five(g.block_table), five(g.seq_lens), five(g.tokens), batch=5,
                        logits=torch.empty((5, 1024), device="cuda"))
     assert e.value.code == -3
+    # the binding itself refuses a block table whose row stride is not the model's, or with too few rows
+    with pytest.raises(ValueError):
+        Bd.decode_step(g.model, g.pool, g.block_table[:, :-1].contiguous(), g.seq_lens, g.tokens)
+    with pytest.raises(ValueError):
+        Bd.decode_step(g.model, g.pool, g.block_table[:3].contiguous(), g.seq_lens, g.tokens)
     bad = g.block_table.clone(); bad[2, 0] = g.pool.num_blocks + 3
     with pytest.raises(Bd.ChironError) as e:
         Bd.validate_step_inputs(g.model, g.pool, bad, g.seq_lens, g.tokens)
