@@ -48,7 +48,10 @@ int32_t launch_pack_rows(const uint16_t* src, int rows, int K, size_t tstride, u
 // weight loads (KS*NF KiB per wave) is always in flight.  Activations are double-buffered in LDS: while chunk c
 // is consumed, chunk c+1 is written to the other buffer and chunk c+2 is on its way from L2 into registers;
 // one barrier per chunk.
-template <int MT, int NF, int KS, int PRO>
+// WNT: weight loads carry the non-temporal hint (every weight is read once: a single M-tile).  With several M-tiles
+// the same weights are read once per M-tile through the L2, and the hint makes those re-reads slower (measured on the
+// 8B gate/up shape at 2048 rows: the weight stream alone 268 us with the hint, 194 us without).
+template <int MT, int NF, int KS, int PRO, bool WNT = true>
 __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE) ? 2 : 1)) void linear_kernel(const uint16_t* __restrict__ Wp, size_t tstride, int Npad, int Nreal, int K, int Kpad,
                                                      const float* __restrict__ A, int lda, int M,
                                                      float* __restrict__ Y, int ldy, int chunks_per_split,
@@ -115,7 +118,8 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
 #pragma unroll
         // non-temporal: a step reads every weight once, and what the weights do not displace stays cached for the
         // activations and the K/V pages (same-device A/B on the whole step: -7 % at 1 request, -1.5 % at 64..2048)
-        for (int f = 0; f < NF; ++f) w[s][f] = load_stream_16(wp[f] + off);
+        for (int f = 0; f < NF; ++f)
+            w[s][f] = WNT ? load_stream_16(wp[f] + off) : *reinterpret_cast<const uint4*>(wp[f] + off);
     };
     // staging task i of a chunk: 8 consecutive k of one row, thread tid + 256*i
     auto load_task = [&](int c, int i, float4 (&ar)[2], float4 (&ur)[2]) {
@@ -390,10 +394,10 @@ Tuning& tuning() {
     return t;
 }
 
-template <int MT, int NF, int PRO, int KS = 4>
+template <int MT, int NF, int PRO, int KS = 4, bool WNT = true>
 static void launch_cfg(int nblocks, hipStream_t st, const Linear& L, const float* A, int lda, int M, float* y, int ldy,
                        int cps, int mode, size_t part_stride, int gx, int gy, int gz) {
-    launch(linear_kernel<MT, NF, KS, PRO>, dim3(nblocks), dim3(256), st, L.w, L.tstride, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode,
+    launch(linear_kernel<MT, NF, KS, PRO, WNT>, dim3(nblocks), dim3(256), st, L.w, L.tstride, L.Npad, L.N, L.K, L.Kpad, A, lda, M, y, ldy, cps, mode,
                                                            part_stride, gx, gy, gz, tuning().linear_xcd_remap);
 }
 
@@ -532,10 +536,14 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
         else if (nf == 1) launch_cfg<2, 1, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else launch_cfg<2, 2, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
     } else if (prologue == PRO_PACKED) {
-        if (nf == 4) launch_cfg<4, 4, PRO_PACKED>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+        // several M-tiles re-read the weights through the L2: no streaming hint then
+        if (nf == 4 && gz > 1) launch_cfg<4, 4, PRO_PACKED, 4, false>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+        else if (nf == 4) launch_cfg<4, 4, PRO_PACKED>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+        else if (gz > 1) launch_cfg<4, 2, PRO_PACKED, 4, false>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else launch_cfg<4, 2, PRO_PACKED>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
     } else if (nf == 4 && prologue != PRO_SWIGLU) {
-        if (mt == 4) launch_cfg<4, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+        if (mt == 4 && gz > 1) launch_cfg<4, 4, PRO_NONE, 4, false>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+        else if (mt == 4) launch_cfg<4, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else launch_cfg<2, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
     } else if (mt == 1 && nf == 1) CHIRON_LAUNCH(1, 1);
     else if (mt == 1) CHIRON_LAUNCH(1, 2);
