@@ -48,6 +48,20 @@ def measured_traffic(workload, kclass):
     return dict(fetch_bytes=fetch, write_bytes=write, total_bytes=fetch + write) if cur == sha else None
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+# the paper's inter-token-latency SLOs (Evaluation: workloads and SLOs): interactive requests 200 ms, batch requests 2 s
+ITL_SLOS_MS = (("interactive", 200.0), ("batch", 2000.0))
+
+
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
@@ -60,7 +74,8 @@ def kernel_algorithmic(m, batch, ctx_tokens):
     M = batch
 
     def gemm(N, K, extra_in=0):
-        return dict(bytes=2 * N * K + 4 * M * (K + extra_in) + 4 * M * N, flops=2 * M * N * K)
+        act = 4 * M * (K + extra_in) + 4 * M * N
+        return dict(bytes=2 * N * K + act, act_bytes=act, flops=2 * M * N * K)
 
     return {
         "qkv": gemm(qn + 2 * kn, H), "o": gemm(H, qn), "gateup": gemm(2 * F, H), "down": gemm(H, F, extra_in=F),
@@ -100,7 +115,7 @@ def cpu_baseline(wl, sample, gpu_logits):
     sig = float(logits.std())
     err = float(np.abs(gpu_logits - logits).max() / sig)
     agree = float((gpu_logits.argmax(1) == logits.argmax(1)).mean())
-    return dict(value=len(sample) / dt, unit="tokens/s", cores=orc.num_threads(), kind="oracle",
+    return dict(value=len(sample) / dt, unit="tokens/s", cores=orc.num_threads(), cpu=cpu_model(), kind="oracle",
                 sample="requests %d..%d of the batch, all %d layers and the LM head, one step (%.1f s)" % (
                     sample[0], sample[-1], wl.m["n_layers"], dt),
                 seconds=dt), dict(rows=len(sample), max_abs_err_over_sigma=err, argmax_agreement=agree)
@@ -198,6 +213,11 @@ def main():
                       "lmhead": "linear_kernel (LM head)", "attn": "paged_attn_kernel"}[dom]
     roof["avg_us"] = d_us
     roof["algorithmic_bytes_per_launch"] = alg[dom]["bytes"]
+    if roof["bound"] == "hbm" and dom != "attn":
+        # the same kernel priced on its weight bytes alone (2*N*K), the figure for a small-M projection
+        wb = alg[dom]["bytes"] - alg[dom]["act_bytes"]
+        roof["weight_bytes_per_launch"] = wb
+        roof["frac_weights_only"] = round(wb / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
     if roof["bound"] == "hbm" and batch == full_batch:
         roof["traffic"] = measured_traffic(a.workload, dom)
 
@@ -233,18 +253,23 @@ def main():
         out["sweep"] = pts
 
     if a.autoscale_slo_ms > 0:
-        # Alg. 1 closed loop: ITL and throughput observed at the current maximum batch size, one update per tick
-        slo, mbs, tput_prev, traj = a.autoscale_slo_ms * 1e-3, 1, 0.0, []
-        for tick in range(64):
-            pt = B.step_latency_profile(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, [mbs], warmup=1, iters=3,
-                                        logits=logits)[0]
-            new, lb = B.local_autoscale_step(pt["lat_ms_median"] * 1e-3, slo, tput_prev, pt["tokens_per_s"], mbs, batch)
-            traj.append(dict(max_batch=mbs, itl_ms=round(pt["lat_ms_median"], 3), tokens_per_s=round(pt["tokens_per_s"], 1),
-                             backpressure=round(lb, 4), next_max_batch=new))
-            log("autoscale tick %2d: batch %4d  ITL %.3f ms  backpressure %.3f -> %d" % (tick, mbs, pt["lat_ms_median"], lb, new))
-            tput_prev = pt["tokens_per_s"] if new > mbs else 0.0   # after a scale-down there is nothing comparable
-            mbs = new
-        out["autoscale"] = dict(itl_slo_ms=a.autoscale_slo_ms, alpha=0.5, trajectory=traj)
+        # Alg. 1 closed loop: ITL and throughput observed at the current maximum batch size, one update per tick, under
+        # both caller policies: "as-printed" keeps the previous tick's throughput for TBP whatever the tick did;
+        # "reset-after-no-growth" passes none after a tick that did not scale up (nothing comparable was observed)
+        runs = {}
+        for policy in ("as-printed", "reset-after-no-growth"):
+            slo, mbs, tput_prev, traj = a.autoscale_slo_ms * 1e-3, 1, 0.0, []
+            for tick in range(64):
+                pt = B.step_latency_profile(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, [mbs], warmup=1, iters=3,
+                                            logits=logits)[0]
+                new, lb = B.local_autoscale_step(pt["lat_ms_median"] * 1e-3, slo, tput_prev, pt["tokens_per_s"], mbs, batch)
+                traj.append(dict(max_batch=mbs, itl_ms=round(pt["lat_ms_median"], 3), tokens_per_s=round(pt["tokens_per_s"], 1),
+                                 backpressure=round(lb, 4), next_max_batch=new))
+                tput_prev = pt["tokens_per_s"] if (policy == "as-printed" or new > mbs) else 0.0
+                mbs = new
+            log("autoscale (%s): batch sizes %s" % (policy, [t["max_batch"] for t in traj]))
+            runs[policy] = traj
+        out["autoscale"] = dict(itl_slo_ms=a.autoscale_slo_ms, alpha=0.5, trajectories=runs)
 
     if a.q_len > 1:
         # verify step of speculative decoding: q_len new tokens per request in one pass (the last q_len-1 cached
@@ -311,7 +336,7 @@ def main():
         torch.cuda.empty_cache()
         t0 = time.time()
         w_host = wl_w_host
-        oracle_sizes = [b for b in (1, 8) if w_host is not None]   # 64 takes ~20 s more: left to `--workload ... --batch 64`
+        oracle_sizes = [b for b in (1, 8, 64) if w_host is not None]
         cw = W.build(CURVE_WORKLOAD, seed=0, model=model, host_seqs=list(range(max(oracle_sizes))) if oracle_sizes else ())
         log("curve workload %s built in %.1f s: %d requests, %d context tokens" % (CURVE_WORKLOAD, time.time() - t0, cbatch, cw.context_tokens))
         clog = torch.empty((cbatch, cm["vocab"]), dtype=torch.float32, device="cuda")
@@ -324,6 +349,15 @@ def main():
             log("curve: batch %4d: %.3f ms  %.0f tok/s  (%.1f%% of the step's roofline)" % (
                 p["batch"], p["lat_ms_median"], p["tokens_per_s"], 100 * p["frac_of_roofline"]))
         out["curve"] = dict(workload=CURVE_WORKLOAD, points=pts)
+        # the curve against the paper's ITL SLOs: the largest measured batch size whose step stays within each
+        slo_rows = []
+        for cls, slo_ms in ITL_SLOS_MS:
+            ok = [p["batch"] for p in pts if p["lat_ms_p99"] <= slo_ms]
+            slo_rows.append(dict(request_class=cls, itl_slo_ms=slo_ms, largest_batch_within_slo=max(ok) if ok else 0,
+                                 step_ms_there=round(max(p["lat_ms_p99"] for p in pts if p["batch"] == max(ok)), 3) if ok else None,
+                                 bounded_by="largest batch measured" if ok and max(ok) == max(sizes) else "the SLO"))
+            log("curve: ITL SLO %.0f ms (%s requests): largest measured batch within it %d" % (slo_ms, cls, max(ok) if ok else 0))
+        out["curve"]["itl_slo"] = slo_rows
         if oracle_sizes:
             # the oracle beside the curve's smallest batch sizes, on the host cores
             sys.path.insert(0, os.path.join(ROOT, "oracle"))
@@ -333,7 +367,7 @@ def main():
             for b in oracle_sizes:
                 n = int(cw.lens[:b].astype(np.int64).sum())
                 _, _, _, dt = sample_step.run(cm, w_host, [(k[:n], v[:n]) for k, v in cw.kv_host], cw.lens[:b], cw.tok[:b])
-                orows.append(dict(batch=b, seconds=round(dt, 3), tokens_per_s=round(b / dt, 3), cores=orc.num_threads()))
+                orows.append(dict(batch=b, seconds=round(dt, 3), tokens_per_s=round(b / dt, 3), cores=orc.num_threads(), cpu=cpu_model()))
                 log("curve: oracle at batch %d: %.2f s = %.2f tokens/s" % (b, dt, b / dt))
             out["curve"]["oracle"] = orows
             out["curve"]["oracle_skipped"] = [b for b in sizes if b not in oracle_sizes]

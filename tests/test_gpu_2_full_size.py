@@ -143,6 +143,38 @@ def test_8b_batch32_long_context(model8b):
     check_workload("llama8b-b32-long32k", model8b, [0, 31], batches=(8,))
 
 
+def test_8b_width_two_layers_every_row_of_batch512():
+    """Every width of the 8B shape (hidden 4096, 32q/8kv heads of 128, FFN 14336, vocabulary 128256) with two layers,
+    all 512 requests of the mixed population against the oracle: max|d|/sigma and the argmax agreement are taken
+    over 512 rows, and every row tile and row position of the large-batch kernels is compared element by element.
+    Prefix batches cross the other row-tile shapes (96-row tiles at 65..96 and 129..192 rows, 128-row tiles above)."""
+    B, W = _mods()
+    t0 = time.time()
+    wl = W.build("llama8b-width-2layers-mixed512", seed=0, host_seqs=list(range(512)), host_weights=True, gain_jitter=0.1,
+                 log=lambda *a: print(*a, flush=True))
+    print("two-layer 8B-width workload built in %.1f s (%d context tokens)" % (time.time() - t0, wl.context_tokens), flush=True)
+    logits = B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens)
+    torch.cuda.synchronize()
+    got = logits.cpu().numpy()
+    want, _, _, dt = sample_step.run(wl.m, wl.w_host, wl.kv_host, wl.lens, wl.tok)
+    sig = want.std()
+    err = np.abs(got - want).max(axis=1) / sig
+    agree = got.argmax(1) == want.argmax(1)
+    print("all 512 rows: max|d|/sigma = %.3e (worst row %d), argmax agreement %d/512, oracle %.1f s" % (
+        err.max(), int(err.argmax()), int(agree.sum()), dt), flush=True)
+    assert err.max() <= STEP_TOL and agree.mean() >= 0.99
+    for b in (65, 150, 257, 400):
+        sub = B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, batch=b).cpu().numpy()
+        e = np.abs(sub - want[:b]).max() / sig
+        a = (sub.argmax(1) == want[:b].argmax(1)).mean()
+        print("prefix batch %d: max|d|/sigma = %.3e, argmax agreement %.4f" % (b, e, a), flush=True)
+        assert e <= STEP_TOL and a >= 0.99
+    wl.pool.close()
+    wl.model.close()
+    del wl
+    torch.cuda.empty_cache()
+
+
 def test_local_autoscaler_closed_loop_on_the_mixed_population(model8b):
     """Alg. 1 driven by the measured curve: ITL = median step latency at the current maximum batch size,
     throughput = batch / ITL, both from chiron_step_latency_profile on prefixes of the 512-request mixed
