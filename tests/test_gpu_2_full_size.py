@@ -70,14 +70,33 @@ def check_workload(name, model8b, sample, batches):
             for a, b in ((bits(k)[L], ok[L]), (bits(v)[L], ov[L])):
                 fa, fb = bf16_to_f32(a), bf16_to_f32(b)
                 assert np.all(np.abs(fa - fb) <= np.abs(fb) * 2.0 ** -7 + 1e-3 * np.abs(fb).max())
-    # a prefix of the batch gives the same rows (this is how the batch-size sweep is run)
+    # a prefix of the batch gives the same rows (this is how the batch-size sweep is run).  Both runs are within
+    # tolerance of the oracle; they differ from each other by the order of partial sums (the tiling depends on the row
+    # count), which is ~1e-4 sigma, except in rows where that moves a new k or v element across a bf16 rounding
+    # boundary: the element lands on the other bf16 neighbour, and the row moves by a few 1e-3 sigma.  Checked here:
+    # every row that differs by more than 2e-3 sigma is a row whose freshly written K/V bits differ between the runs.
+    def new_slot_bits(rows):
+        out = {}
+        for i in rows:
+            L = int(wl.lens[i])
+            last_page = wl.block_table[i][L // 16:].contiguous()   # the row from the page that holds position L on
+            out[i] = [np.concatenate([bits(t)[L % 16].ravel() for t in wl.pool.gather(l, last_page, L % 16 + 1)])
+                      for l in range(wl.m["n_layers"])]
+        return out
     for b in batches:
         sub = B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, batch=b)
-        d = (sub - logits[:b]).abs().max().item() / sig
-        print("prefix batch %d vs full batch: max|d|/sigma = %.2e" % (b, d), flush=True)
-        # both runs are within tolerance of the oracle; a row whose new k/v element rounds to the other bf16
-        # neighbour in one of them (summation order differs with the tiling) moves by a few 1e-3 sigma
-        assert d <= 1e-2
+        drow = ((sub - logits[:b]).abs().amax(dim=1) / sig).cpu().numpy()
+        moved = [int(i) for i in np.nonzero(drow > 2e-3)[0]]
+        print("prefix batch %d vs full batch: max|d|/sigma = %.2e, rows above 2e-3: %s" % (b, drow.max(), moved), flush=True)
+        assert drow.max() <= 1e-2
+        if moved:
+            bits_prefix = new_slot_bits(moved)
+            B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens)   # the full batch again: rewrites every new slot
+            bits_full = new_slot_bits(moved)
+            for i in moved:
+                flipped = sum(int((a != c).sum()) for a, c in zip(bits_prefix[i], bits_full[i]))
+                print("  row %d: %d new k/v elements on different bf16 neighbours" % (i, flipped), flush=True)
+                assert flipped > 0, "row %d moved by %.1e sigma without a differing k/v element" % (i, drow[i])
     wl.pool.close()
     del wl
     torch.cuda.empty_cache()
