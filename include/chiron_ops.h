@@ -65,7 +65,7 @@ int32_t chiron_op_paged_attention(chiron_model *m, const chiron_kvpool *p, int32
  *   linear_nf (1|2|4), linear_mt (1|2|3|4), linear_xcd_remap (0|1), linear_ksplit, linear_target_blocks,
  *   linear_big_min_m (rows from which a projection's input is first split into tiled bf16 terms; <0 never),
  *   linear_big_all (1: every projection takes that path from there on, not only the SwiGLU one),
- *   linear_ks (4|8: k-steps per chunk, the depth of the weight ring),
+ *   linear_ks (4|8|16: k-steps per chunk, the depth of the weight ring),
  *   attn_grid, attn_target_waves, attn_chunk_pages.
  * They change launch shapes only, never results beyond summation order. Unknown keys are an error. */
 int32_t chiron_set_tuning(const char *key, int32_t value);

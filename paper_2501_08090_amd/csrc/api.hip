@@ -47,7 +47,7 @@ static int32_t linear_alloc(Linear& L, int N, int K) {
     L.N = N;
     L.K = K;
     L.Npad = (N + 31) / 32 * 32;
-    L.Kpad = (K + 127) / 128 * 128;
+    L.Kpad = (K + 255) / 256 * 256;  // whole chunks of the deepest weight ring (16 k-steps of 16)
     L.owned = true;
     L.tstride = (size_t)32 * L.Kpad;
     const size_t bytes = (size_t)(L.Npad / 32) * L.tstride * 2;
@@ -155,7 +155,7 @@ int32_t chiron_model_create(const chiron_model_config* cfg, chiron_model** out) 
     TRY(dev_alloc((void**)&m->qb, (size_t)B * qn * 4));
     TRY(dev_alloc((void**)&m->part, (size_t)linear_max_split() * B * std::max(qn + 2 * kn, H) * 4));
     if (B >= kBigWorkspaceMinBatch) {
-        const size_t kmax = (size_t)(std::max(std::max(F, H), qn) + 127) / 128 * 128;
+        const size_t kmax = (size_t)(std::max(std::max(F, H), qn) + 255) / 256 * 256;
         TRY(dev_alloc((void**)&m->asplit, 2 * linear_big_split_elems(B, (int)kmax) * 2));
     }
     TRY(dev_alloc((void**)&m->x_bt, (size_t)B * cfg->max_blocks_per_seq * 4));
@@ -695,7 +695,7 @@ int32_t chiron_set_tuning(const char* key, int32_t value) {
         {"linear_xcd_remap", &t.linear_xcd_remap, 0, 1, 0u}, {"linear_ksplit", &t.linear_ksplit, 0, 16, 0u},
         {"linear_target_blocks", &t.linear_target_blocks, 1, 1 << 20, 0u},
         {"linear_big_min_m", &t.linear_big_min_m, -1, 1 << 30, 0u}, {"linear_big_all", &t.linear_big_all, 0, 1, 0u},
-        {"linear_ks", &t.linear_ks, 0, 8, 0x111u},        {"attn_grid", &t.attn_grid, 0, 1 << 16, 0u},
+        {"linear_ks", &t.linear_ks, 0, 16, 0x10111u},        {"attn_grid", &t.attn_grid, 0, 1 << 16, 0u},
         {"attn_target_waves", &t.attn_target_waves, 0, 1 << 24, 0u}, {"attn_chunk_pages", &t.attn_chunk_pages, 0, 1 << 20, 0u}};
     for (auto& e : tab)
         if (!strcmp(e.k, key)) {

@@ -59,7 +59,7 @@ inline void launch(void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t st, 
 // Weight W [N,K] (out,in) is stored as 32-row tiles, each tile as K/8 groups of [32 rows][8 k] bf16:
 //   packed[((n/32)*(Kpad/8) + k/8)*256 + (n%32)*8 + k%8] = W[n][k]
 // so one 32x16 MFMA operand fragment (two adjacent k-groups) is 1 KiB of contiguous memory.  N is padded to a
-// multiple of 32 and K to a multiple of 128 with zeros, so the kernel's loads need no bounds checks.
+// multiple of 32 and K to a multiple of 256 with zeros, so the kernel's loads need no bounds checks.
 struct Linear {
     uint16_t* w = nullptr;  // device, packed and zero-padded
     int N = 0, K = 0, Npad = 0, Kpad = 0;
@@ -78,7 +78,7 @@ struct Tuning {
     int linear_ksplit = 0;          // forced number of K-slices
     int linear_target_blocks = 256; // K is sliced until the grid has about this many workgroups
     int linear_big_min_m = 0;       // rows from which the input is pre-split into tiled bf16 terms (0 = built-in, <0 = never)
-    int linear_ks = 0;              // k-steps of 16 per chunk (depth of the weight ring): 4 or 8
+    int linear_ks = 0;              // k-steps of 16 per chunk (depth of the weight ring): 4, 8 or 16
     int linear_big_all = 0;         // 1: pre-split every projection's input from that row count on, not only the SwiGLU one
     int attn_grid = 0;              // workgroups of the persistent attention grid
     int attn_target_waves = 0;      // work items aimed for when one round of the grid cannot hold the list (0 = 4 rounds)

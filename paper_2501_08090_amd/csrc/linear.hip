@@ -519,7 +519,12 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     // the weight bytes in flight per wave, which measured 9 % faster on the gate/up shape at 64 rows.
     const bool ks8 = (mt == 2 || (mt == 3 && nf == 1 && prologue == PRO_NONE)) && nf <= 2 && prologue != PRO_PACKED &&
                      (tn.linear_ks == 8 || (tn.linear_ks == 0 && nf == 1 && !part && prologue == PRO_NONE));
-    const int KC = ks8 ? 128 : 64;
+    // Up to 32 rows a wave has two MFMAs per k-step and its weight stream is bound by the bytes it keeps in flight over
+    // the load latency: the unsliced one-tile-per-wave shape takes a ring of 16 k-steps (16 KiB per wave; measured on the
+    // 8B gate/up shape: 37.3 against 40.0 us at one row, 39.8 against 41.4 us at 32 rows; no gain at 64 rows)
+    const bool ks16 = mt == 1 && nf == 1 && prologue == PRO_NONE && L.Kpad % 256 == 0 &&
+                      (tn.linear_ks == 16 || (tn.linear_ks == 0 && !part));
+    const int KC = ks16 ? 256 : (ks8 ? 128 : 64);
     int chunks = (L.K + KC - 1) / KC;
     int ksplit = tn.linear_ksplit ? tn.linear_ksplit : (tn.linear_target_blocks + gx * gz - 1) / (gx * gz);
     // never a few workgroups more than one per CU: the CUs that get a second one take twice as long (264 workgroups
@@ -551,7 +556,9 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
         else                                                                                                            \
             launch_cfg<MT_, NF_, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz); \
     } while (0)
-    if (ks8 && mt == 3) {
+    if (ks16) {
+        launch_cfg<1, 1, PRO_NONE, 16>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+    } else if (ks8 && mt == 3) {
         launch_cfg<3, 1, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
     } else if (ks8) {
         if (prologue == PRO_SWIGLU) launch_cfg<2, 2, PRO_SWIGLU, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);

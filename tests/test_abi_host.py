@@ -70,7 +70,7 @@ def test_null_handles_are_invalid_arguments():
     for key, bad in ((b"linear_nf", 3), (b"linear_nf", 8), (b"linear_mt", 5), (b"linear_mt", -1), (b"linear_ks", 6),
                      (b"linear_ksplit", 17), (b"attn_grid", -1), (b"linear_xcd_remap", 2), (b"attn_chunk_pages", -2)):
         assert lib.chiron_set_tuning(key, bad) == -1 and b"not allowed" in lib.chiron_last_error()
-    for key, ok in ((b"linear_nf", 4), (b"linear_mt", 3), (b"linear_ks", 8), (b"linear_big_min_m", -1), (b"attn_grid", 7)):
+    for key, ok in ((b"linear_nf", 4), (b"linear_mt", 3), (b"linear_ks", 8), (b"linear_ks", 16), (b"linear_big_min_m", -1), (b"attn_grid", 7)):
         assert lib.chiron_set_tuning(key, ok) == 0
         assert lib.chiron_set_tuning(key, 0) == 0
     assert lib.chiron_model_destroy(z) == 0 and lib.chiron_kv_pool_destroy(z) == 0 and lib.chiron_linear_destroy(z) == 0
