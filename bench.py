@@ -28,9 +28,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "9ea43d6ce8f3b5dec18572d9db92b9d78c49fc1f9cf2fa199c8deccfc2654ece", 275762673, 4259900),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "62b703260792182421d6b4af86cd56400c658f67d70fdf32d953bb316f213c9a", 125044594, 16777228),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "62b703260792182421d6b4af86cd56400c658f67d70fdf32d953bb316f213c9a", 243437715, 7340032),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "9ea43d6ce8f3b5dec18572d9db92b9d78c49fc1f9cf2fa199c8deccfc2654ece", 275771900, 4259906),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "86840ff2334c1a164389e1c3887c25aac8c7f3b1eb370b842b0597f8f486e455", 125037157, 16777224),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "86840ff2334c1a164389e1c3887c25aac8c7f3b1eb370b842b0597f8f486e455", 243441252, 7340032),
+    ("llama8b-mixed-sweep512", "attn"): ("attention.hip", "9ea43d6ce8f3b5dec18572d9db92b9d78c49fc1f9cf2fa199c8deccfc2654ece", 4204299961, 37314251),
+    ("llama8b-b32-long32k", "attn"): ("attention.hip", "9ea43d6ce8f3b5dec18572d9db92b9d78c49fc1f9cf2fa199c8deccfc2654ece", 3721964532, 29757940),
 }
 
 
@@ -218,7 +220,7 @@ def main():
         wb = alg[dom]["bytes"] - alg[dom]["act_bytes"]
         roof["weight_bytes_per_launch"] = wb
         roof["frac_weights_only"] = round(wb / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
-    if roof["bound"] == "hbm" and batch == full_batch:
+    if batch == full_batch:
         roof["traffic"] = measured_traffic(a.workload, dom)
 
     step_bytes = W.algorithmic_bytes(m, wl.lens, batch)
