@@ -129,7 +129,10 @@ def test_rmsnorm(rows, n):
 @pytest.mark.parametrize("M,N,K", [(1, 256, 256), (4, 512, 256), (4, 1376, 256), (4, 256, 688), (33, 96, 1040),
                                    (64, 1024, 4096), (100, 160, 512), (130, 4096, 1024), (7, 1000, 64),
                                    (400, 8192, 512), (385, 2080, 256), (70, 512, 256), (96, 1376, 4096), (65, 4096, 512),
-                                   (150, 1376, 256), (270, 4096, 512), (300, 28672, 256)])
+                                   (150, 1376, 256), (270, 4096, 512), (300, 28672, 256),
+                                   # wide unsliced outputs of up to 32 rows take the 16-step weight ring (256-wide chunks):
+                                   # one chunk, several chunks, a ragged last chunk
+                                   (8, 20000, 256), (1, 17000, 1040), (32, 16416, 784), (17, 28672, 2048)])
 def test_linear(M, N, K):
     rng = np.random.default_rng(M * 7 + N * 3 + K)
     x = rng.standard_normal((M, K)).astype(np.float32)
