@@ -145,7 +145,7 @@ def main():
                          "population that is otherwise measured after the step (kernel profiles of the step use this)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
+        print("bench.py: the library runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
               "Replicas scale by running one instance per GPU." % a.gpus, file=sys.stderr)
         sys.exit(2)
 
