@@ -104,7 +104,8 @@ def population(kind, n, seed=0):
     """Context lengths (tokens already cached) of n requests.
     tiny: U{16..128};  b64: lognormal median 800 in [64,4096];  mixed: 70% interactive (lognormal median 512 in
     [16,8192]) / 30% batch (U{2048..8192}), request j is batch-class iff j mod 10 in {3,6,9};
-    interactive: the interactive class alone;
+    interactive: the interactive class alone;  short: lognormal median 256 in [16,2048] (what lets 4096 requests'
+    caches fit one GPU);
     b128-70b: lognormal median 2048 in [128,8192];  long: U{24576..32768}."""
     rng = np.random.default_rng(_sub_seed(seed, "population", kind))
     if kind == "tiny":
@@ -118,6 +119,8 @@ def population(kind, n, seed=0):
         return np.where(is_batch, batch, inter).astype(np.int32)
     if kind == "interactive":
         return lognormal_lengths(n, 512, 16, 8192, rng)
+    if kind == "short":
+        return lognormal_lengths(n, 256, 16, 2048, rng)
     if kind == "b128-70b":
         return lognormal_lengths(n, 2048, 128, 8192, rng)
     if kind == "long":

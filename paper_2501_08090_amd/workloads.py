@@ -25,11 +25,14 @@ WORKLOADS = {
     # the batch sizes the paper reports for batch-class instances (2048-4096) on what one GPU's HBM holds:
     # interactive-length contexts only (a 2048-request mixed population would need 270 GB of cache)
     "llama8b-interactive-sweep2048": (I.LLAMA_8B, "interactive", 2048, 1.05),
+    # 4096 requests, the upper end of the batch sizes the paper reports for batch-class instances: contexts short enough
+    # (lognormal median 256) that their caches fit beside the weights
+    "llama8b-short-sweep4096": (I.LLAMA_8B, "short", 4096, 1.05),
     # every width of the 8B shape (hidden, heads, FFN, vocabulary) with two layers only, so that a CPU checker can
     # afford all 512 rows of the mixed population: every row tile of the large-batch kernels, element by element
     "llama8b-width-2layers-mixed512": (dict(I.LLAMA_8B, name="llama3-8b-width-2-layers", n_layers=2), "mixed", 512, 1.15),
 }
-SWEEP_BATCHES = (1, 8, 32, 64, 128, 256, 512, 1024, 2048)
+SWEEP_BATCHES = (1, 8, 32, 64, 128, 256, 512, 1024, 2048, 4096)
 KV_CHUNK_TOKENS = 1 << 17
 
 

@@ -28,7 +28,7 @@ def _mods():
 def model8b():
     B, W = _mods()
     t0 = time.time()
-    model, w_host = W.build_model(I.LLAMA_8B, seed=0, max_batch=2048, max_blocks_per_seq=2049, host_weights=True,
+    model, w_host = W.build_model(I.LLAMA_8B, seed=0, max_batch=4096, max_blocks_per_seq=2049, host_weights=True,
                                   log=lambda *a: print(*a, flush=True))
     print("8B model built in %.1f s" % (time.time() - t0), flush=True)
     yield model, w_host
@@ -156,6 +156,17 @@ def test_8b_batch2048_interactive_population(model8b):
     lens = I.population("interactive", 2048, 0)
     sample = sorted({0, int(lens.argmin()), int(lens.argmax()), 1023, 2047})
     check_workload("llama8b-interactive-sweep2048", model8b, sample, batches=(1024,))
+
+
+def test_8b_batch4096_short_population(model8b):
+    """The upper end of the batch sizes the paper reports for batch-class instances (2048-4096): 4096 requests with
+    short contexts (lognormal, median 256 tokens), 190 GB of cache; 32 M-tiles of the large-batch projection kernels."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < 225e9:
+        pytest.skip("needs 225 GB of free HBM, %.0f GB available" % (free / 1e9))
+    lens = I.population("short", 4096, 0)
+    sample = sorted({0, int(lens.argmin()), int(lens.argmax()), 2047, 4095})
+    check_workload("llama8b-short-sweep4096", model8b, sample, batches=(3000,))
 
 
 def test_8b_batch32_long_context(model8b):
