@@ -104,7 +104,7 @@ def check_workload(name, model8b, sample, batches):
 
 def test_8b_batch64_lognormal(model8b):
     lens = I.population("b64", 64, 0)
-    sample = sorted({0, 1, int(lens.argmin()), int(lens.argmax()), 31, 63})
+    sample = sorted({0, 1, int(lens.argmin()), int(lens.argmax()), 31, 63} | set(range(5, 64, 7)))   # 15 of the 64 rows
     check_workload("llama8b-b64-lognormal800", model8b, sample, batches=(1, 8, 33))
 
 
@@ -143,7 +143,7 @@ def test_8b_batch64_multi_token_step(model8b):
 
 def test_8b_batch512_mixed_population(model8b):
     lens = I.population("mixed", 512, 0)
-    sample = sorted({0, 3, int(lens.argmin()), 255, 511})
+    sample = sorted({0, 3, int(lens.argmin()), 255, 511} | set(range(40, 512, 67)))   # 12 rows across the four 128-row tiles
     check_workload("llama8b-mixed-sweep512", model8b, sample, batches=(1, 128))
 
 
