@@ -11,8 +11,12 @@
 // merges the items of a request.
 //
 // The work list is built on the device from seq_lens (the host never sees the lengths), and the
-// attention grid is persistent: each wave strides over the list, which has a fixed length in
-// memory, so every wave terminates.
+// attention grid is persistent: a wave starts on the item of its own index and then draws the
+// index of each further item from a ticket counter, one item ahead, so that waves whose items
+// were short (the ragged last run of a request) take more of them.  There are eight counters,
+// each on a cache line of its own and each serving every eighth item and every eighth workgroup
+// (one counter takes about 50 M draws a second, too few for lists of small items).  Tickets only
+// grow and the list has a fixed length in memory, so every wave terminates.
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
@@ -29,10 +33,15 @@ namespace chiron {
 // Last, 32-byte aligned, one record of 8 ints per item: {pass, first page, attended length, the ids of the item's
 // first four pages (past its end: its last page), 0}: everything a wave needs before its first tile load, in one
 // scalar load instead of a chain of four dependent ones (the block table does not differ between layers).
+// After the records, kTicketQueues ticket counters kTicketStride ints apart, all 0 between attention launches.
 __host__ __device__ inline int64_t plan_rec_offset(int max_batch, int cap_items) {
     return (4 + 2 * (int64_t)max_batch + 2 * (int64_t)cap_items + 7) / 8 * 8;
 }
-int64_t attn_plan_ints(int max_batch, int cap_items) { return plan_rec_offset(max_batch, cap_items) + 8 * (int64_t)cap_items; }
+constexpr int kTicketQueues = 8, kTicketStride = 64;
+__host__ __device__ inline int64_t plan_ticket_offset(int max_batch, int cap_items) {
+    return (plan_rec_offset(max_batch, cap_items) + 8 * (int64_t)cap_items + kTicketStride - 1) / kTicketStride * kTicketStride;
+}
+int64_t attn_plan_ints(int max_batch, int cap_items) { return plan_ticket_offset(max_batch, cap_items) + kTicketQueues * kTicketStride; }
 
 AttnShape attn_shape(int G, int q_len, int len_bias) {
     AttnShape sh;
@@ -62,6 +71,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(int32_t* __rest
     int32_t* item_seq = plan + 4 + 2 * max_batch;
     int32_t* item_pg0 = item_seq + cap_items;
     const int tid = threadIdx.x;
+    if (tid < kTicketQueues) plan[plan_ticket_offset(max_batch, cap_items) + tid * kTicketStride] = 0;
     const int per = (batch + kPlanThreads - 1) / kPlanThreads;  // requests per thread, contiguous
     const int i0 = tid * per, i1 = min(batch, i0 + per);
 
@@ -168,10 +178,11 @@ int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const
 // group of tv <= tg tokens: operand column t*G + h is query head h of the group's token t, which sees positions
 // < len - (tv-1) + t of the pass's len; the request's pages are read once per pass (G*tg <= 16 columns).
 template <int D, int G, bool MULTI>
-__global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, const float* __restrict__ q, int ldq, AttnShape sh,
+__global__ __launch_bounds__(256, 2) void paged_attn_kernel(PoolDesc p, int layer, const float* __restrict__ q, int ldq, AttnShape sh,
                                                          const int32_t* __restrict__ bt, int max_blocks,
                                                          const int32_t* __restrict__ seq_lens,
-                                                         const int32_t* __restrict__ plan, int max_batch, int cap_items,
+                                                         const int32_t* __restrict__ plan, int32_t* __restrict__ tickets,
+                                                         int max_batch, int cap_items,
                                                          float* __restrict__ part_o, float* __restrict__ part_ml,
                                                          float scale_log2e) {
     constexpr int KSTEPS = D / 32;  // 16x16x32 MFMAs per score tile; also 16-byte V fragments per page
@@ -204,7 +215,11 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
         b3_nx = __builtin_amdgcn_readfirstlane(r[6]);
     };
     fetch_rec(w / n_kv);
-    for (; w < n_work; w += n_waves) {
+    const bool draw = n_work > n_waves;  // one round holds everything: no second item for anybody
+    // queue j hands out the indices n_waves + j, n_waves + j + nq, ... to the workgroups j, j + nq, ...
+    const int nq = gridDim.x >= kTicketQueues ? kTicketQueues : 1, qj = blockIdx.x % nq;
+    int32_t* ticket = tickets + qj * kTicketStride;
+    while (w < n_work) {
         const int it = w / n_kv, c = w - it * n_kv;
         const int pg0 = pg0_nx, len = len_nx;
         const int first_ids[4] = {b0_nx, b1_nx, b2_nx, b3_nx};
@@ -316,8 +331,11 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
         load_group(kc, vc);   // the first tiles are on their way before anything else of the item is touched
         blk_next[0] = first_ids[2];
         blk_next[1] = first_ids[3];
+        // the next item's index: drawn now, read after the q loads below have returned (memory operations return in
+        // order, so by then the draw costs no wait of its own)
+        int drawn = 0;
+        if (draw && lane == 0) drawn = atomicAdd(ticket, 1);
         __builtin_amdgcn_sched_barrier(0);
-        fetch_rec((w + n_waves) / n_kv);  // next item's record, needed only after this item is done
         // q fragments: operand column = head, 8 consecutive dims per lane group; scaled by log2(e)/sqrt(d)
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
@@ -332,6 +350,8 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
                 qh[s] = ql[s] = make_uint4(0, 0, 0, 0);
             }
         }
+        const int w_next = draw ? n_waves + __builtin_amdgcn_readfirstlane(drawn) * nq + qj : n_work;
+        fetch_rec(w_next / n_kv);  // next item's record, needed only after this item is done
         int pg = pg0;
         for (; pg + NPG < pg1; pg += NPG) {
             load_group(kn, vn);
@@ -362,6 +382,7 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
             for (int t = 0; t < D / 16; ++t)
                 *reinterpret_cast<float4*>(part_o + slot * D + t * 16 + lg * 4) = make_float4(o[t][0], o[t][1], o[t][2], o[t][3]);
         }
+        w = w_next;
     }
 }
 
@@ -369,7 +390,8 @@ __global__ __launch_bounds__(256) void paged_attn_kernel(PoolDesc p, int layer, 
 // 256 threads = 8 item slices x 32 lanes of float4 (D = 128) or 16 slices x 16 lanes (D = 64); slice k takes
 // items k, k+S, ...; the slices are combined through LDS in a fixed order.
 template <int D>
-__global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restrict__ plan, int max_batch, int n_kv, int G, AttnShape sh,
+__global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restrict__ plan, int32_t* __restrict__ tickets,
+                                                          int max_batch, int n_kv, int G, AttnShape sh,
                                                           const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml, float* __restrict__ out,
                                                           int ldo) {
@@ -382,6 +404,8 @@ __global__ __launch_bounds__(256) void attn_reduce_kernel(const int32_t* __restr
     const int a = blockIdx.y, c = a / G, j = (t % sh.tg) * G + a % G, GT = G * sh.tg;
     const int sl = threadIdx.x / LANES, ln = threadIdx.x % LANES;
     const int item0 = plan[4 + v], nch = plan[4 + max_batch + v];
+    // the attention kernel before this one has drained: its ticket counters go back to 0 for the next one
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < kTicketQueues) tickets[threadIdx.x * kTicketStride] = 0;
     // each slice folds its items with a running maximum, two items' loads in flight at a time
     float M = -INFINITY, den = 0.f;
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -434,15 +458,16 @@ template <int D>
 static int32_t launch_attn_d(int G, dim3 grid, hipStream_t st, const PoolDesc& p, int layer, const float* q, int ldq,
                              const AttnShape& sh, const int32_t* bt, int max_blocks, const int32_t* seq_lens,
                              const AttnWorkspace& ws, float scale) {
+    int32_t* tickets = ws.plan + plan_ticket_offset(ws.max_batch, ws.cap_items);
 #define CHIRON_ATTN(G_)                                                                                              \
     do {                                                                                                             \
         if (sh.q_len > 1)                                                                                            \
             launch(paged_attn_kernel<D, G_, true>, dim3(grid), dim3(256), st, p, layer, q, ldq, sh, bt, max_blocks, seq_lens,     \
-                                                                 ws.plan, ws.max_batch, ws.cap_items, ws.part_o,     \
+                                                                 ws.plan, tickets, ws.max_batch, ws.cap_items, ws.part_o,     \
                                                                  ws.part_ml, scale);                                 \
         else                                                                                                         \
             launch(paged_attn_kernel<D, G_, false>, dim3(grid), dim3(256), st, p, layer, q, ldq, sh, bt, max_blocks, seq_lens,    \
-                                                                  ws.plan, ws.max_batch, ws.cap_items, ws.part_o,    \
+                                                                  ws.plan, tickets, ws.max_batch, ws.cap_items, ws.part_o,    \
                                                                   ws.part_ml, scale);                                \
     } while (0)
     switch (G) {
@@ -482,8 +507,9 @@ int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, c
     if (batch == 0) return CHIRON_OK;
     const int G = n_q / p.n_kv;
     dim3 rgrid(batch * sh.q_len, n_q);
-    if (p.d == 128) launch(attn_reduce_kernel<128>, dim3(rgrid), dim3(256), st, ws.plan, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
-    else launch(attn_reduce_kernel<64>, dim3(rgrid), dim3(256), st, ws.plan, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
+    int32_t* tickets = ws.plan + plan_ticket_offset(ws.max_batch, ws.cap_items);
+    if (p.d == 128) launch(attn_reduce_kernel<128>, dim3(rgrid), dim3(256), st, ws.plan, tickets, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
+    else launch(attn_reduce_kernel<64>, dim3(rgrid), dim3(256), st, ws.plan, tickets, ws.max_batch, p.n_kv, G, sh, ws.part_o, ws.part_ml, out, ldo);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }

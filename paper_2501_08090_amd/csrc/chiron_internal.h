@@ -139,7 +139,7 @@ int32_t launch_rope_append(const PoolDesc& p, int layer, const float* qkv, int k
 
 // ---- paged attention ------------------------------------------------------------------------------
 struct AttnWorkspace {
-    int32_t* plan = nullptr;     // [0]=n_items, [1]=chunk_pages; then per-seq and per-item tables (see attention.hip)
+    int32_t* plan = nullptr;     // [0]=n_items, [1]=chunk_pages; then per-seq and per-item tables, ticket counters (see attention.hip)
     float* part_o = nullptr;     // [items*n_kv][tg*G][d], items*tg <= cap_items
     float* part_ml = nullptr;    // [items*n_kv][tg*G][2]
     int cap_items = 0, max_batch = 0;
@@ -159,6 +159,8 @@ AttnShape attn_shape(int G, int q_len, int len_bias);
 // (bt: the block table the attention launches of this plan will use; the plan copies each item's first page ids)
 int32_t launch_attn_plan(const AttnWorkspace& ws, const int32_t* seq_lens, const int32_t* bt, int max_blocks, const AttnShape& sh,
                          int batch, int n_kv, hipStream_t st);
+// launch_attn_main leaves the plan's ticket counters used; launch_attn_merge, which must follow it on the same stream
+// before the next launch_attn_main, puts them back to 0.
 int32_t launch_attn_main(const AttnWorkspace& ws, const PoolDesc& p, int layer, const float* q, int ldq, int n_q,
                          const int32_t* bt, int max_blocks, const int32_t* seq_lens, const AttnShape& sh, int batch,
                          hipStream_t st);

@@ -257,11 +257,13 @@ def test_paged_attention(d, nq, nkv, lens):
         assert np.abs(got - want).max() <= KERNEL_TOL * max(1.0, np.abs(want).max())
 
 
-@pytest.mark.parametrize("grid,chunk", [(4, 0), (4, 3), (2, 1), (0, 5)])
+@pytest.mark.parametrize("grid,chunk", [(4, 0), (4, 3), (2, 1), (0, 5), (8, 2), (24, 1)])
 def test_paged_attention_work_list_over_several_rounds(grid, chunk):
     """A small persistent grid (grid workgroups = 4*grid wave slots) makes every wave walk several items of the work
-    list, whose records are fetched one item ahead; forced chunk sizes give items of 1, 3 or 5 pages with ragged
-    ends.  24 requests of 1..1500 cached tokens, 4 query heads per KV head."""
+    list: its own first, then items whose indices it draws from ticket counters (one counter below 8 workgroups, eight
+    from there on), records fetched one item ahead; forced chunk sizes give items of 1, 2, 3 or 5 pages with ragged
+    ends.  24 requests of 1..1500 cached tokens, 4 query heads per KV head.  The call is made twice and must give the
+    same bits (the counters' state between the layers of one step is covered by the multi-layer steps at batch 512)."""
     d, nq, nkv = 128, 8, 2
     rng = np.random.default_rng(41)
     lens = rng.integers(1, 1500, size=24).astype(np.int32)
@@ -277,6 +279,7 @@ def test_paged_attention_work_list_over_several_rounds(grid, chunk):
     try:
         print("attention grid", grid, "chunk", chunk, flush=True)
         got = b.op_paged_attention(g.model, g.pool, 0, torch.from_numpy(q).cuda(), g.block_table, g.seq_lens).cpu().numpy()
+        again = b.op_paged_attention(g.model, g.pool, 0, torch.from_numpy(q).cuda(), g.block_table, g.seq_lens).cpu().numpy()
     finally:
         b.set_tuning("attn_grid", 0)
         b.set_tuning("attn_chunk_pages", 0)
@@ -284,6 +287,7 @@ def test_paged_attention_work_list_over_several_rounds(grid, chunk):
                      for i in range(len(lens))])
     assert np.all(np.isfinite(got))
     assert np.abs(got - want).max() <= KERNEL_TOL * max(1.0, np.abs(want).max())
+    assert np.array_equal(got, again)  # which wave takes which item does not enter the result
 
 
 # ---- the whole step ---------------------------------------------------------------------------------
