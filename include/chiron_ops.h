@@ -33,11 +33,23 @@ int32_t chiron_linear_destroy(chiron_linear *l);
 int32_t chiron_op_linear(const chiron_linear *l, const float *x, int32_t M, float *y, int32_t accumulate,
                          void *stream);
 
-/* SwiGLU fused into the projection's operand load: with gu dev fp32 [M, 2K] holding the gate
- * values in columns [0,K) and the up values in [K,2K),
- *     y (+)= (silu(gate) * up) * W^T,   silu(z) = z / (1 + exp(-z)). */
-int32_t chiron_op_swiglu_linear(const chiron_linear *l, const float *gu, int32_t M, float *y, int32_t accumulate,
-                                void *stream);
+/* The fused gate/up matrix of a feed-forward block: w_gate, w_up dev bf16 [F, K] each, row-major, F and K multiples
+ * of 16.  The library's copy interleaves the two so that gate column j and up column j are produced by one wave; it
+ * goes with the two SwiGLU entry points below only (chiron_op_linear refuses it). */
+int32_t chiron_linear_create_gate_up(const void *w_gate, const void *w_up, int32_t F, int32_t K, void *stream,
+                                     chiron_linear **out);
+
+/* SwiGLU fused into the gate/up projection's epilogue:
+ *     act[m][j] = silu(gate[m][j]) * up[m][j],  gate = x * Wg^T,  up = x * Wu^T,  silu(z) = z / (1 + exp(-z)).
+ * x dev fp32 [M, K]; act dev fp32 [M, F], caller-owned. */
+int32_t chiron_op_gate_up_swiglu(const chiron_linear *gate_up, const float *x, int32_t M, float *act, void *stream);
+
+/* The feed-forward block as the decode step runs it, two launches:  y (+)= act * Wd^T  with act as above.
+ * down is a plain chiron_linear over Wd [N, F].  The intermediate never leaves the library: fp32 rows with few rows,
+ * and from the row count of the linear_big_min_m knob on the two bf16 terms of act in the tile order that the down
+ * projection copies straight into LDS.  x dev fp32 [M, K]; y dev fp32 [M, N]. */
+int32_t chiron_op_swiglu_ffn(const chiron_linear *gate_up, const chiron_linear *down, const float *x, int32_t M,
+                             float *y, int32_t accumulate, void *stream);
 
 /* Rotary embedding in place: x dev fp32 [rows, n_heads, d]; row r is rotated for position pos[r]
  * (pairs (j, j+d/2), angle pos*base^(-2j/d), angles evaluated in fp64). */
@@ -63,8 +75,8 @@ int32_t chiron_op_paged_attention(chiron_model *m, const chiron_kvpool *p, int32
 
 /* Performance knobs of the kernels, process-wide (0 restores the built-in heuristic where one exists):
  *   linear_nf (1|2|4), linear_mt (1|2|3|4), linear_xcd_remap (0|1), linear_ksplit, linear_target_blocks,
- *   linear_big_min_m (rows from which a projection's input is first split into tiled bf16 terms; <0 never),
- *   linear_big_all (1: every projection takes that path from there on, not only the SwiGLU one),
+ *   linear_big_min_m (rows from which the gate/up projection hands the down projection tiled bf16 terms; <0 never),
+ *   linear_big_all (1: from that row count on every other projection's input is split into such terms first),
  *   linear_ks (4|8|16: k-steps per chunk, the depth of the weight ring),
  *   attn_grid, attn_target_waves, attn_chunk_pages.
  * They change launch shapes only, never results beyond summation order. Unknown keys are an error. */

@@ -24,7 +24,7 @@ SYMBOLS = [
     "chiron_decode_step", "chiron_decode_step_multi", "chiron_validate_step_inputs", "chiron_check_step_inputs_host",
     "chiron_validate_step_inputs_multi", "chiron_check_step_inputs_host_multi", "chiron_step_latency_profile",
     "chiron_last_error", "chiron_kernel_timing_begin", "chiron_kernel_timing_end", "chiron_local_autoscale_step",
-    "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_op_swiglu_linear",
+    "chiron_op_rmsnorm", "chiron_linear_create", "chiron_linear_destroy", "chiron_op_linear", "chiron_linear_create_gate_up", "chiron_op_gate_up_swiglu", "chiron_op_swiglu_ffn",
     "chiron_op_rope", "chiron_op_rope_noalloc", "chiron_op_paged_attention", "chiron_set_tuning",
 ]
 
@@ -306,14 +306,6 @@ class Linear:
                                        C.c_int32(1 if accumulate else 0), _stream()))
         return y
 
-    def swiglu(self, gu, y=None, accumulate=False):
-        M = gu.shape[0]
-        if y is None:
-            y = torch.empty((M, self.N), dtype=torch.float32, device="cuda")
-        _check(load().chiron_op_swiglu_linear(self._h, _ptr(gu, torch.float32), C.c_int32(M), _ptr(y, torch.float32),
-                                              C.c_int32(1 if accumulate else 0), _stream()))
-        return y
-
     def close(self):
         if self._h:
             torch.cuda.synchronize()
@@ -325,6 +317,38 @@ class Linear:
             self.close()
         except Exception:
             pass
+
+
+class GateUp(Linear):
+    """The fused gate/up matrix of a feed-forward block (w_gate, w_up [F, K] bf16)."""
+
+    def __init__(self, w_gate, w_up):
+        self.F, self.K = w_gate.shape
+        if tuple(w_up.shape) != (self.F, self.K):
+            raise ValueError("w_gate and w_up differ in shape")
+        self.N = 2 * self.F
+        self._h = C.c_void_p()
+        _check(load().chiron_linear_create_gate_up(_ptr(w_gate, torch.bfloat16), _ptr(w_up, torch.bfloat16), C.c_int32(self.F),
+                                                   C.c_int32(self.K), _stream(), C.byref(self._h)))
+
+    def __call__(self, x, *a, **k):
+        raise TypeError("a fused gate/up matrix has no plain product: use swiglu() or ffn()")
+
+    def swiglu(self, x):
+        """silu(x Wg^T) * (x Wu^T), fp32 [M, F]"""
+        M = x.shape[0]
+        act = torch.empty((M, self.F), dtype=torch.float32, device="cuda")
+        _check(load().chiron_op_gate_up_swiglu(self._h, _ptr(x, torch.float32), C.c_int32(M), _ptr(act, torch.float32), _stream()))
+        return act
+
+    def ffn(self, down, x, y=None, accumulate=False):
+        """y (+)= (silu(x Wg^T) * (x Wu^T)) Wd^T with down = Linear(Wd)"""
+        M = x.shape[0]
+        if y is None:
+            y = torch.empty((M, down.N), dtype=torch.float32, device="cuda")
+        _check(load().chiron_op_swiglu_ffn(self._h, down._h, _ptr(x, torch.float32), C.c_int32(M), _ptr(y, torch.float32),
+                                           C.c_int32(1 if accumulate else 0), _stream()))
+        return y
 
 
 def set_tuning(key, value):

@@ -156,12 +156,16 @@ int32_t chiron_model_create(const chiron_model_config* cfg, chiron_model** out) 
     TRY(dev_alloc((void**)&m->part, (size_t)linear_max_split() * B * std::max(qn + 2 * kn, H) * 4));
     if (B >= kBigWorkspaceMinBatch) {
         const size_t kmax = (size_t)(std::max(std::max(F, H), qn) + 255) / 256 * 256;
-        TRY(dev_alloc((void**)&m->asplit, 2 * linear_big_split_elems(B, (int)kmax) * 2));
+        const size_t bytes = 2 * linear_big_split_elems(B, (int)kmax) * 2;
+        TRY(dev_alloc((void**)&m->asplit, bytes));
+        // the gate/up epilogue writes the columns below F only: what the down projection reads of its K padding is 0
+        if (hipMemset(m->asplit, 0, bytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess)
+            TRY(fail(CHIRON_ERR_HIP, "clearing the activation workspace failed"));
     }
     TRY(dev_alloc((void**)&m->x_bt, (size_t)B * cfg->max_blocks_per_seq * 4));
     TRY(dev_alloc((void**)&m->x_lens, (size_t)B * 4));
     TRY(dev_alloc((void**)&m->attn, (size_t)B * qn * 4));
-    TRY(dev_alloc((void**)&m->gub, (size_t)B * 2 * F * 4));
+    TRY(dev_alloc((void**)&m->gub, (size_t)B * F * 4));  // silu(gate) * up, fp32 rows
     TRY(dev_alloc((void**)&m->cos_t, (size_t)B * (d / 2) * 4));
     TRY(dev_alloc((void**)&m->sin_t, (size_t)B * (d / 2) * 4));
     // attention work list: room for a few items per wave slot plus one ragged tail per request
@@ -184,13 +188,13 @@ int32_t chiron_model_load_layer(chiron_model* m, int32_t layer, const chiron_lay
     const chiron_model_config& c = m->cfg;
     const int H = c.hidden, d = c.head_dim, F = c.ffn, qn = c.n_q_heads * d, kn = c.n_kv_heads * d;
     int32_t rc;
-    // fused QKV: rows [q | k | v]; fused gate/up: rows [gate | up]
+    // fused QKV: rows [q | k | v]; fused gate/up: 16 gate and the 16 up columns of the same indices per 32-row tile
     if ((rc = launch_pack_rows((const uint16_t*)w->wq, qn, H, m->qkv[layer].tstride, m->qkv[layer].w, 0, st))) return rc;
     if ((rc = launch_pack_rows((const uint16_t*)w->wk, kn, H, m->qkv[layer].tstride, m->qkv[layer].w, qn, st))) return rc;
     if ((rc = launch_pack_rows((const uint16_t*)w->wv, kn, H, m->qkv[layer].tstride, m->qkv[layer].w, qn + kn, st))) return rc;
     if ((rc = launch_pack_rows((const uint16_t*)w->wo, H, qn, m->wo[layer].tstride, m->wo[layer].w, 0, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->w_gate, F, H, m->gu[layer].tstride, m->gu[layer].w, 0, st))) return rc;
-    if ((rc = launch_pack_rows((const uint16_t*)w->w_up, F, H, m->gu[layer].tstride, m->gu[layer].w, F, st))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_gate, F, H, m->gu[layer].tstride, m->gu[layer].w, 0, st, 1))) return rc;
+    if ((rc = launch_pack_rows((const uint16_t*)w->w_up, F, H, m->gu[layer].tstride, m->gu[layer].w, 0, st, 2))) return rc;
     if ((rc = launch_pack_rows((const uint16_t*)w->w_down, H, F, m->down[layer].tstride, m->down[layer].w, 0, st))) return rc;
     CHIRON_HIP(hipMemcpyAsync(m->attn_norm + (size_t)layer * H, w->attn_norm, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
     CHIRON_HIP(hipMemcpyAsync(m->ffn_norm + (size_t)layer * H, w->ffn_norm, (size_t)H * 2, hipMemcpyDeviceToDevice, st));
@@ -299,6 +303,9 @@ static int32_t check_step_args(const chiron_model* m, const chiron_kvpool* p, co
     return CHIRON_OK;
 }
 
+// whether the feed-forward block's intermediate takes the tiled two-term form (needs the workspace for it)
+static bool ffn_packed(const Linear& down, int M, const uint16_t* asplit) { return asplit && M >= linear_big_min_rows(down); }
+
 // One pass of the model over B rows.  Row r carries token tokens[r] at position seq_lens[r] of the request whose
 // pages block_table row r lists.  With q_len == 1 a row is a request.  With q_len > 1 rows r = i*q_len + t are the
 // new tokens of request i (expanded index arrays), and attention runs per request over (req_bt, req_lens, B/q_len):
@@ -343,8 +350,17 @@ static int32_t step_rows(chiron_model* m, chiron_kvpool* p, const int32_t* block
         STEP(CHIRON_K_O, launch_linear(m->wo[l], m->attn, qn, B, m->h, H, 1, PRO_NONE, m->part, msplit, &ks_res, m->asplit, st));
         if (ks_res == 1) ks_res = 0;  // written straight into h
         STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->ffn_norm + (size_t)l * H, B, H, c.rms_eps, m->x, st));
-        STEP(CHIRON_K_GATEUP, launch_linear(m->gu[l], m->x, H, B, m->gub, 2 * F, 0, PRO_NONE, nullptr, 1, nullptr, m->asplit, st));
-        STEP(CHIRON_K_DOWN, launch_linear(m->down[l], m->gub, 2 * F, B, m->h, H, 1, PRO_SWIGLU, m->part, msplit, &ks_res, m->asplit, st));
+        // a = silu(x Wg) * (x Wu) leaves the gate/up projection as fp32 rows, or, with many rows, as the tiled bf16 terms
+        // that the down projection copies straight into LDS
+        if (ffn_packed(m->down[l], B, m->asplit)) {
+            STEP(CHIRON_K_GATEUP, launch_linear(m->gu[l], m->x, H, B, reinterpret_cast<float*>(m->asplit), m->down[l].Kpad, EPI_SWIGLU_PACKED,
+                                                PRO_NONE, nullptr, 1, nullptr, nullptr, st));
+            STEP(CHIRON_K_DOWN, launch_linear(m->down[l], reinterpret_cast<const float*>(m->asplit), 0, B, m->h, H, EPI_ADD, PRO_PACKED,
+                                              m->part, msplit, &ks_res, nullptr, st));
+        } else {
+            STEP(CHIRON_K_GATEUP, launch_linear(m->gu[l], m->x, H, B, m->gub, F, EPI_SWIGLU, PRO_NONE, nullptr, 1, nullptr, m->asplit, st));
+            STEP(CHIRON_K_DOWN, launch_linear(m->down[l], m->gub, F, B, m->h, H, EPI_ADD, PRO_NONE, m->part, msplit, &ks_res, m->asplit, st));
+        }
         if (ks_res == 1) ks_res = 0;
     }
     STEP(CHIRON_K_RMSNORM, launch_rmsnorm(m->h, m->part, ks_res, m->final_norm, B, H, c.rms_eps, m->x, st));
@@ -542,6 +558,26 @@ int32_t chiron_linear_create(const void* w, int32_t N, int32_t K, void* stream, 
     return CHIRON_OK;
 }
 
+int32_t chiron_linear_create_gate_up(const void* w_gate, const void* w_up, int32_t F, int32_t K, void* stream, chiron_linear** out) {
+    if (!out) return fail(CHIRON_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (!w_gate || !w_up || F < 1 || K < 1) return fail(CHIRON_ERR_INVALID_ARG, "gate/up: null weight or non-positive size");
+    if (K % 16 != 0 || F % 16 != 0) return fail(CHIRON_ERR_SHAPE, "gate/up: K=%d and F=%d must be multiples of 16", K, F);
+    chiron_linear* l = new (std::nothrow) chiron_linear();
+    if (!l) return fail(CHIRON_ERR_OOM, "host allocation failed");
+    l->gate_up = true;
+    int32_t rc = linear_alloc(l->L, 2 * F, K);
+    if (!rc) rc = launch_pack_rows((const uint16_t*)w_gate, F, K, l->L.tstride, l->L.w, 0, (hipStream_t)stream, 1);
+    if (!rc) rc = launch_pack_rows((const uint16_t*)w_up, F, K, l->L.tstride, l->L.w, 0, (hipStream_t)stream, 2);
+    if (rc) {
+        linear_free(l->L);
+        delete l;
+        return rc;
+    }
+    *out = l;
+    return CHIRON_OK;
+}
+
 int32_t chiron_linear_destroy(chiron_linear* l) {
     if (l) {
         linear_free(l->L);
@@ -560,9 +596,10 @@ static int32_t op_linear_common(const Linear& L, const float* x, int lda, int M,
     const bool may_split = L.N <= 16384;
     if (may_split) CHIRON_HIP(hipMallocAsync((void**)&part, (size_t)msplit * M * L.N * sizeof(float), st));
     uint16_t* asplit = nullptr;
-    if (M >= linear_big_min_rows(L)) CHIRON_HIP(hipMallocAsync((void**)&asplit, 2 * linear_big_split_elems(M, L.Kpad) * 2, st));
+    if (prologue == PRO_NONE && tuning().linear_big_all && M >= linear_big_min_rows(L))
+        CHIRON_HIP(hipMallocAsync((void**)&asplit, 2 * linear_big_split_elems(M, L.Kpad) * 2, st));
     int ks = 1;
-    int32_t rc = launch_linear(L, x, lda, M, y, L.N, accumulate, prologue, part, msplit, &ks, asplit, st);
+    int32_t rc = launch_linear(L, x, lda, M, y, L.N, accumulate ? EPI_ADD : EPI_STORE, prologue, part, msplit, &ks, asplit, st);
     if (asplit) (void)hipFreeAsync(asplit, st);
     if (!rc && ks > 1) rc = launch_reduce_partials(part, ks, (int64_t)M * L.N, y, accumulate, st);
     if (part) (void)hipFreeAsync(part, st);
@@ -574,16 +611,47 @@ int32_t chiron_op_linear(const chiron_linear* l, const float* x, int32_t M, floa
     if (M < 0) return fail(CHIRON_ERR_INVALID_ARG, "M is negative");
     if (M == 0) return CHIRON_OK;
     if (!x || !y) return fail(CHIRON_ERR_INVALID_ARG, "linear: a pointer is null");
+    if (l->gate_up) return fail(CHIRON_ERR_INVALID_ARG, "linear: a fused gate/up matrix goes with the SwiGLU entry points only");
     return op_linear_common(l->L, x, l->L.K, M, y, accumulate, PRO_NONE, (hipStream_t)stream);
 }
 
-int32_t chiron_op_swiglu_linear(const chiron_linear* l, const float* gu, int32_t M, float* y, int32_t accumulate,
-                                void* stream) {
-    if (!l) return fail(CHIRON_ERR_INVALID_ARG, "linear is null");
+int32_t chiron_op_gate_up_swiglu(const chiron_linear* gate_up, const float* x, int32_t M, float* act, void* stream) {
+    if (!gate_up) return fail(CHIRON_ERR_INVALID_ARG, "linear is null");
     if (M < 0) return fail(CHIRON_ERR_INVALID_ARG, "M is negative");
     if (M == 0) return CHIRON_OK;
-    if (!gu || !y) return fail(CHIRON_ERR_INVALID_ARG, "swiglu_linear: a pointer is null");
-    return op_linear_common(l->L, gu, 2 * l->L.K, M, y, accumulate, PRO_SWIGLU, (hipStream_t)stream);
+    if (!x || !act) return fail(CHIRON_ERR_INVALID_ARG, "gate_up_swiglu: a pointer is null");
+    if (!gate_up->gate_up) return fail(CHIRON_ERR_INVALID_ARG, "gate_up_swiglu: the matrix was not created as a fused gate/up matrix");
+    const Linear& L = gate_up->L;
+    return launch_linear(L, x, L.K, M, act, L.N / 2, EPI_SWIGLU, PRO_NONE, nullptr, 1, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int32_t chiron_op_swiglu_ffn(const chiron_linear* gate_up, const chiron_linear* down, const float* x, int32_t M, float* y,
+                             int32_t accumulate, void* stream) {
+    if (!gate_up || !down) return fail(CHIRON_ERR_INVALID_ARG, "linear is null");
+    if (M < 0) return fail(CHIRON_ERR_INVALID_ARG, "M is negative");
+    if (M == 0) return CHIRON_OK;
+    if (!x || !y) return fail(CHIRON_ERR_INVALID_ARG, "swiglu_ffn: a pointer is null");
+    if (!gate_up->gate_up || down->gate_up) return fail(CHIRON_ERR_INVALID_ARG, "swiglu_ffn: wants a fused gate/up matrix and a plain one");
+    const Linear &G = gate_up->L, &D = down->L;
+    const int F = G.N / 2;
+    if (D.K != F) return fail(CHIRON_ERR_SHAPE, "swiglu_ffn: gate/up has %d columns, the down projection %d inputs", F, D.K);
+    hipStream_t st = (hipStream_t)stream;
+    // the intermediate in the form the decode step gives it at this row count
+    const bool packed = M >= linear_big_min_rows(D);
+    const size_t bytes = packed ? 2 * linear_big_split_elems(M, D.Kpad) * 2 : (size_t)M * F * 4;
+    void* act = nullptr;
+    CHIRON_HIP(hipMallocAsync(&act, bytes, st));
+    int32_t rc = CHIRON_OK;
+    if (packed) {
+        if (hipMemsetAsync(act, 0, bytes, st) != hipSuccess) rc = fail(CHIRON_ERR_HIP, "clearing the activation workspace failed");
+        if (!rc) rc = launch_linear(G, x, G.K, M, (float*)act, D.Kpad, EPI_SWIGLU_PACKED, PRO_NONE, nullptr, 1, nullptr, nullptr, st);
+        if (!rc) rc = op_linear_common(D, (const float*)act, 0, M, y, accumulate, PRO_PACKED, st);
+    } else {
+        rc = launch_linear(G, x, G.K, M, (float*)act, F, EPI_SWIGLU, PRO_NONE, nullptr, 1, nullptr, nullptr, st);
+        if (!rc) rc = op_linear_common(D, (const float*)act, F, M, y, accumulate, PRO_NONE, st);
+    }
+    (void)hipFreeAsync(act, st);
+    return rc;
 }
 
 int32_t chiron_op_rope(float* x, int32_t rows, int32_t n_heads, int32_t d, const int32_t* pos, float base, void* stream) {

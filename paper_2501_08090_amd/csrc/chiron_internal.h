@@ -68,7 +68,12 @@ struct Linear {
 };
 
 // PRO_PACKED: the input is already split into its two bf16 terms and tiled (see linear_big.hip)
-enum Prologue { PRO_NONE = 0, PRO_SWIGLU = 1, PRO_PACKED = 2 };
+enum Prologue { PRO_NONE = 0, PRO_PACKED = 2 };
+// What a projection does with its result.  EPI_SLICES is chosen inside launch_linear when it slices K.  The SwiGLU
+// epilogues belong to a fused gate/up matrix packed with launch_pack_rows(..., interleave): the output has N/2 columns,
+// out[m][j] = silu(gate[m][j]) * up[m][j], as fp32 rows (EPI_SWIGLU) or as the two bf16 terms in the tile order that
+// PRO_PACKED reads (EPI_SWIGLU_PACKED: y is the base of the hi terms, ldy the padded K of the consuming projection).
+enum Epilogue { EPI_STORE = 0, EPI_ADD = 1, EPI_SLICES = 2, EPI_SWIGLU = 3, EPI_SWIGLU_PACKED = 4 };
 
 // Performance knobs (0 = built-in heuristic); see chiron_set_tuning.
 struct Tuning {
@@ -77,31 +82,34 @@ struct Tuning {
     int linear_xcd_remap = 1;       // deal logical workgroup ids XCD by XCD (M-tiles of one weight tile share an L2)
     int linear_ksplit = 0;          // forced number of K-slices
     int linear_target_blocks = 256; // K is sliced until the grid has about this many workgroups
-    int linear_big_min_m = 0;       // rows from which the input is pre-split into tiled bf16 terms (0 = built-in, <0 = never)
+    int linear_big_min_m = 0;       // rows from which the down projection's input is written as tiled bf16 terms (0 = built-in, <0 = never)
     int linear_ks = 0;              // k-steps of 16 per chunk (depth of the weight ring): 4, 8 or 16
-    int linear_big_all = 0;         // 1: pre-split every projection's input from that row count on, not only the SwiGLU one
+    int linear_big_all = 0;         // 1: pre-split every projection's input from that row count on, not only the down projection's
     int attn_grid = 0;              // workgroups of the persistent attention grid
     int attn_target_waves = 0;      // work items aimed for when one round of the grid cannot hold the list (0 = 4 rounds)
     int attn_chunk_pages = 0;       // forced pages per item
 };
 Tuning& tuning();
 
-// C[M,N] = A[M,K] * W^T.  A is fp32 with row stride lda.  PRO_SWIGLU: A[m][k] = silu(src[m][k]) * src[m][K+k].
+// C[M,N] = A[M,K] * W^T.  A is fp32 with row stride lda (PRO_NONE), or the tiled bf16 terms of it (PRO_PACKED: hi terms
+// at A, lo terms linear_big_split_elems(M, L.Kpad) bf16 values further).
 // If the launch slices K (only when `part` is given; at most max_split slices), slice s stores its partial product
 // at part[s][M][N] and *ksplit_out = number of slices: the caller's consumer adds them up.  Otherwise the result
-// goes to y (y += if accumulate) and *ksplit_out = 1.
-// `asplit` (optional) is a workspace of 2 * linear_big_split_elems(M, L.Kpad) bf16 values: with it, launches of many
-// rows first store the two bf16 terms of A there in tile order (launch_linear_big) and multiply from those.
-int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
+// goes to y as `epilogue` (EPI_STORE, EPI_ADD, or a SwiGLU epilogue, which never slices) says and *ksplit_out = 1.
+// `asplit` (optional) is a workspace of 2 * linear_big_split_elems(M, L.Kpad) bf16 values: with it and the
+// linear_big_all knob, launches of many rows first store the two bf16 terms of A there (launch_linear_big).
+int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int epilogue, int prologue,
                       float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st);
-int32_t launch_linear_big(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
+int32_t launch_linear_big(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int epilogue,
                           float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st);
 size_t linear_big_split_elems(int M, int Kpad);
 int linear_big_min_rows(const Linear& L);
 int linear_max_split();
 int32_t launch_reduce_partials(const float* part, int ks, int64_t n, float* y, int accumulate, hipStream_t st);
+// interleave: 0 = source row r becomes packed row row_offset + r; 1 / 2 = the source is the gate / up half of a fused
+// gate/up matrix, whose 32-row tiles hold 16 gate and the 16 up columns of the same indices (rows % 16 == 0)
 int32_t launch_pack_rows(const uint16_t* src, int rows, int K, size_t tstride, uint16_t* dst_packed, int row_offset,
-                         hipStream_t st);
+                         hipStream_t st, int interleave = 0);
 
 // ---- elementwise / indexing kernels ---------------------------------------------------------------
 int32_t launch_embed(const uint16_t* table, const int32_t* tokens, int batch, int H, float* h, hipStream_t st);
@@ -171,6 +179,7 @@ int32_t launch_attn_merge(const AttnWorkspace& ws, const PoolDesc& p, int n_q, c
 
 struct chiron_linear {
     chiron::Linear L;
+    bool gate_up = false;  // rows are the interleaved [gate | up] of a feed-forward block
 };
 
 struct chiron_kvpool {

@@ -11,6 +11,12 @@
 //
 // PRO_PACKED (large batches, see linear_big.hip): the activations arrive already split into their two bf16
 // terms in tile order and are copied global -> LDS directly, without staging registers or conversion work.
+//
+// The gate/up projection of the feed-forward block ends in SwiGLU: its weights are packed so that every 32-column
+// tile holds 16 gate columns and the 16 up columns of the same indices (gate_up_packed_row below), which puts
+// gate[m][j] and up[m][j] into the two halves of one wave, and the epilogue writes silu(gate) * up, either as fp32
+// rows or already split into bf16 terms in the tile order that PRO_PACKED reads.  The down projection then is a plain
+// projection over half the bytes, and nothing evaluates exp() more than once per element.
 #include <climits>
 #include <cstdlib>
 
@@ -20,24 +26,33 @@
 namespace chiron {
 
 // ---- weight repacking -------------------------------------------------------------------------------
+// Packed row of gate (kind 0) or up (kind 1) column j in the fused gate/up matrix.  Row i of a 32-row tile lands in
+// accumulator register r of the lanes of half h with i = 8*(r/4) + 4*h + r%4: the gate column 16*tile + r goes to
+// half 0, register r, the up column of the same index to half 1, register r.
+__host__ __device__ inline int gate_up_packed_row(int j, int kind) {
+    return 32 * (j / 16) + 8 * ((j % 16) / 4) + 4 * kind + j % 4;
+}
+
+// interleave: 0 = rows go to row_offset + r; 1 / 2 = r is a gate / up column of a fused gate/up matrix
 __global__ __launch_bounds__(256) void pack_rows_kernel(const uint16_t* __restrict__ src, int rows, int K, size_t tstride,
-                                                        uint16_t* __restrict__ dst, int row_offset) {
+                                                        uint16_t* __restrict__ dst, int row_offset, int interleave) {
     int kgroups = K / 8;
     int64_t total = (int64_t)rows * kgroups;
     for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
         int r = (int)(t / kgroups), kg = (int)(t % kgroups);
-        int n = r + row_offset;
+        int n = interleave ? gate_up_packed_row(r, interleave - 1) : r + row_offset;
         uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)r * K + (size_t)kg * 8);
         *reinterpret_cast<uint4*>(dst + (size_t)(n / 32) * tstride + (size_t)kg * 256 + (size_t)(n % 32) * 8) = v;
     }
 }
 
 int32_t launch_pack_rows(const uint16_t* src, int rows, int K, size_t tstride, uint16_t* dst_packed, int row_offset,
-                         hipStream_t st) {
+                         hipStream_t st, int interleave) {
     if (rows == 0) return CHIRON_OK;
+    if (interleave && rows % 16 != 0) return fail(CHIRON_ERR_SHAPE, "gate/up packing: %d columns are not a multiple of 16", rows);
     int64_t total = (int64_t)rows * (K / 8);
     int blocks = (int)((total + 255) / 256 < 8192 ? (total + 255) / 256 : 8192);
-    launch(pack_rows_kernel, dim3(blocks), dim3(256), st, src, rows, K, tstride, dst_packed, row_offset);
+    launch(pack_rows_kernel, dim3(blocks), dim3(256), st, src, rows, K, tstride, dst_packed, row_offset, interleave);
     CHIRON_HIP(hipGetLastError());
     return CHIRON_OK;
 }
@@ -97,7 +112,6 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
 
     uint4 w[KS][NF];
     float4 areg[TPT][2];  // fp32 staging registers (unused with PRO_PACKED, whose input goes straight into LDS)
-    float4 ureg[PRO == PRO_SWIGLU ? TPT : 1][2];
     // PRO_PACKED: A points at the hi terms in 32-row x 8-k tile order, the lo terms follow them
     const int mtiles_all = (M + 31) / 32;
     const float4* Ahi = reinterpret_cast<const float4*>(A);
@@ -122,28 +136,19 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
             w[s][f] = WNT ? load_stream_16(wp[f] + off) : *reinterpret_cast<const uint4*>(wp[f] + off);
     };
     // staging task i of a chunk: 8 consecutive k of one row, thread tid + 256*i
-    auto load_task = [&](int c, int i, float4 (&ar)[2], float4 (&ur)[2]) {
+    auto load_task = [&](int c, int i, float4 (&ar)[2]) {
         int task = tid + i * 256;
         int kg = task % KG, m = task / KG;
         int k = c * KC + kg * 8;
         const float* p = A + (size_t)min(m0 + m, M - 1) * lda + min(k, K - 8);
         ar[0] = *reinterpret_cast<const float4*>(p);
         ar[1] = *reinterpret_cast<const float4*>(p + 4);
-        if (PRO == PRO_SWIGLU) {
-            ur[0] = *reinterpret_cast<const float4*>(p + K);
-            ur[1] = *reinterpret_cast<const float4*>(p + K + 4);
-        }
     };
-    auto stage_task = [&](int c, int i, int buf, const float4 (&ar)[2], const float4 (&ur)[2]) {
+    auto stage_task = [&](int c, int i, int buf, const float4 (&ar)[2]) {
         int task = tid + i * 256;
         int kg = task % KG, m = task / KG;
         const bool ok = (m0 + m < M) && (c * KC + kg * 8 < K);
         float v[8] = {ar[0].x, ar[0].y, ar[0].z, ar[0].w, ar[1].x, ar[1].y, ar[1].z, ar[1].w};
-        if (PRO == PRO_SWIGLU) {
-            float u[8] = {ur[0].x, ur[0].y, ur[0].z, ur[0].w, ur[1].x, ur[1].y, ur[1].z, ur[1].w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = v[e] / (1.0f + __expf(-v[e])) * u[e];
-        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = ok ? v[e] : 0.f;
         uint4 hi, lo;
@@ -156,11 +161,11 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
     };
     auto load_a = [&](int c) {
 #pragma unroll
-        for (int i = 0; i < TPT; ++i) load_task(c, i, areg[i], ureg[PRO == PRO_SWIGLU ? i : 0]);
+        for (int i = 0; i < TPT; ++i) load_task(c, i, areg[i]);
     };
     auto stage_a = [&](int c, int buf) {
 #pragma unroll
-        for (int i = 0; i < TPT; ++i) stage_task(c, i, buf, areg[i], ureg[PRO == PRO_SWIGLU ? i : 0]);
+        for (int i = 0; i < TPT; ++i) stage_task(c, i, buf, areg[i]);
     };
     // PRO_PACKED: chunk c of the pre-split activations goes HBM/L2 -> LDS directly (16 bytes per lane, a wave
     // fills 64 consecutive rows of one k-group), no registers and no LDS store instructions in between
@@ -277,9 +282,9 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
             // chunk's tasks follow in the loop's order, so that the wait counts of entry and back edge agree.  (Two
             // chunks or more and a single chunk are separate paths: in one path the compiler moves the second chunk's
             // loads, which only the loop uses, behind the barrier and out of that order.)
-            float4 a0[TPT][2], u0[PRO == PRO_SWIGLU ? TPT : 1][2];
+            float4 a0[TPT][2];
 #pragma unroll
-            for (int i = 0; i < TPT; ++i) load_task(c_begin, i, a0[i], u0[PRO == PRO_SWIGLU ? i : 0]);
+            for (int i = 0; i < TPT; ++i) load_task(c_begin, i, a0[i]);
             __builtin_amdgcn_sched_barrier(0);
             if (c_begin < c_last) {
 #pragma unroll
@@ -289,12 +294,12 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
 #pragma unroll
                     for (int i = 0; i < TPT; ++i)
                         if (i * KS / TPT == s) {
-                            load_task(c_begin + 1, i, areg[i], ureg[PRO == PRO_SWIGLU ? i : 0]);
+                            load_task(c_begin + 1, i, areg[i]);
                             __builtin_amdgcn_sched_barrier(0);
                         }
                 }
 #pragma unroll
-                for (int i = 0; i < TPT; ++i) stage_task(c_begin, i, 0, a0[i], u0[PRO == PRO_SWIGLU ? i : 0]);
+                for (int i = 0; i < TPT; ++i) stage_task(c_begin, i, 0, a0[i]);
                 lds_barrier();
                 int buf = 0, c = c_begin;
                 do {
@@ -306,9 +311,9 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
 #pragma unroll
                         for (int i = 0; i < TPT; ++i)
                             if (i * KS / TPT == s) {
-                                stage_task(c + 1, i, buf ^ 1, areg[i], ureg[PRO == PRO_SWIGLU ? i : 0]);
+                                stage_task(c + 1, i, buf ^ 1, areg[i]);
                                 __builtin_amdgcn_sched_barrier(0);
-                                load_task(min(c + 2, c_last), i, areg[i], ureg[PRO == PRO_SWIGLU ? i : 0]);
+                                load_task(min(c + 2, c_last), i, areg[i]);
                                 __builtin_amdgcn_sched_barrier(0);
                             }
                     }
@@ -321,7 +326,7 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
 #pragma unroll
                 for (int s = 0; s < KS; ++s) load_w(c_begin, s);
 #pragma unroll
-                for (int i = 0; i < TPT; ++i) stage_task(c_begin, i, 0, a0[i], u0[PRO == PRO_SWIGLU ? i : 0]);
+                for (int i = 0; i < TPT; ++i) stage_task(c_begin, i, 0, a0[i]);
                 lds_barrier();
 #pragma unroll
                 for (int s = 0; s < KS; ++s) mma_step(0, s);
@@ -360,6 +365,45 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
 
     // D[i][j]: lane holds column j = lane%32 (an activation row m) and rows i = 8*(r/4) + 4*(lane/32) + r%4
     // (output columns n) for r = 0..15.
+    if (mode >= EPI_SWIGLU) {
+        // Fused gate/up: in tile T the lanes of half 0 hold gate[m][16T + r], those of half 1 up[m][16T + r].  The halves
+        // swap eight values each, after which half h owns the columns 16T + 8h .. + 7 of row m.
+        const int half = lane >> 5;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            const int tile = tile0 + f;
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float mine_g = acc[f][t][e], mine_u = acc[f][t][8 + e];  // half 0: gate e, (gate 8+e); half 1: (up e), up 8+e
+                    const float got = __shfl_xor(half ? mine_g : mine_u, 32);       // half 0 receives up e, half 1 gate 8+e
+                    const float g = half ? got : mine_g, u = half ? mine_u : got;
+                    v[e] = g / (1.0f + __expf(-g)) * u;
+                }
+                const int m = m0 + t * 32 + (lane & 31);
+                if (m >= M || tile >= Npad / 32) continue;
+                if (mode == EPI_SWIGLU) {
+                    float* dst = Y + (size_t)m * ldy + tile * 16 + half * 8;
+                    *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                    *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+                } else {
+                    // the two bf16 terms in 32-row x 8-k tile order (ldy = k-groups of the consumer, part_stride = distance
+                    // from the hi to the lo terms in 16-byte units)
+                    uint4 hi, lo;
+                    split2(v[0], v[1], hi.x, lo.x);
+                    split2(v[2], v[3], hi.y, lo.y);
+                    split2(v[4], v[5], hi.z, lo.z);
+                    split2(v[6], v[7], hi.w, lo.w);
+                    uint4* dst = reinterpret_cast<uint4*>(Y) + ((size_t)(m / 32) * ldy + (size_t)(2 * tile + half)) * 32 + (m & 31);
+                    dst[0] = hi;
+                    dst[part_stride] = lo;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
         int nb = (tile0 + f) * 32 + (lane >> 5) * 4;
@@ -367,15 +411,15 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
         for (int t = 0; t < MT; ++t) {
             int m = m0 + t * 32 + (lane & 31);
             if (m >= M) continue;
-            // mode 0: y = acc;  1: y += acc (this workgroup is the only writer);  2: slice blockIdx.y of the workspace
-            float* yrow = Y + (mode == 2 ? (size_t)by * part_stride : (size_t)0) + (size_t)m * ldy;
+            // EPI_STORE: y = acc;  EPI_ADD: y += acc (this workgroup is the only writer);  EPI_SLICES: slice `by` of the workspace
+            float* yrow = Y + (mode == EPI_SLICES ? (size_t)by * part_stride : (size_t)0) + (size_t)m * ldy;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 int n = nb + q * 8;
                 if (n + 3 < Nreal && (ldy & 3) == 0) {
                     float4 v = make_float4(acc[f][t][q * 4], acc[f][t][q * 4 + 1], acc[f][t][q * 4 + 2], acc[f][t][q * 4 + 3]);
                     float4* dst = reinterpret_cast<float4*>(yrow + n);
-                    if (mode == 1) {
+                    if (mode == EPI_ADD) {
                         float4 o = *dst;
                         v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
                     }
@@ -385,7 +429,7 @@ __global__ __launch_bounds__(256, (MT * NF <= 8 && !(MT == 4 && PRO != PRO_NONE)
                     for (int e = 0; e < 4; ++e)
                         if (n + e < Nreal) {
                             float v = acc[f][t][q * 4 + e];
-                            yrow[n + e] = mode == 1 ? yrow[n + e] + v : v;
+                            yrow[n + e] = mode == EPI_ADD ? yrow[n + e] + v : v;
                         }
                 }
             }
@@ -425,23 +469,33 @@ static void launch_cfg(int nblocks, hipStream_t st, const Linear& L, const float
 
 int linear_max_split() { return 16; }
 
-// Rows from which the SwiGLU projection is faster with its input pre-split (launch_linear_big).  In the fused
-// kernel every 256-column workgroup re-reads (and re-evaluates) gate and up for its K-slice: 8 bytes per element
-// against 4 for the pre-split terms, over twice as many workgroup columns.  Measured crossover: above 96 rows at
-// K = 14336 (45 against 51 us at 112 and 128 rows), from 96 rows at K = 28672.
-static int big_min_rows_default(const Linear& L) { return L.K >= 16384 ? 96 : 97; }
+// Rows from which the down projection is faster on the tiled two-term form of its input (128-row tiles, copied straight
+// into LDS) than on fp32 rows (64- and 96-row tiles, split on the way into LDS); the gate/up epilogue writes whichever
+// is asked for.  Measured inside the step, gate/up + down per layer: at K = 14336 (N = 4096) fp32 rows win up to 320
+// rows (160 rows: 138 against 155 us), the two are level at 384..512, the tiled form wins from 768 (533 against 556 us);
+// at K = 28672 (N = 8192) fp32 rows win at 96 rows (92 against 100 us), the tiled form at 128 (102 against 108 us).
+static int big_min_rows_default(const Linear& L) { return L.K >= 16384 ? 97 : 513; }
 
 int linear_big_min_rows(const Linear& L) {
     const int v = tuning().linear_big_min_m;
     return v == 0 ? big_min_rows_default(L) : (v < 0 ? INT32_MAX : v);
 }
 
-int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
+int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int epilogue, int prologue,
                       float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st) {
     if (ksplit_out) *ksplit_out = 1;
     if (M == 0) return CHIRON_OK;
-    if (asplit && prologue != PRO_PACKED && M >= linear_big_min_rows(L) && (prologue == PRO_SWIGLU || tuning().linear_big_all))
-        return launch_linear_big(L, A, lda, M, y, ldy, accumulate, prologue, part, max_split, ksplit_out, asplit, st);
+    if (epilogue != EPI_STORE && epilogue != EPI_ADD && epilogue != EPI_SWIGLU && epilogue != EPI_SWIGLU_PACKED)
+        return fail(CHIRON_ERR_INVALID_ARG, "linear: unknown epilogue %d", epilogue);
+    if (epilogue >= EPI_SWIGLU) {
+        // gate and up of one column must meet in one workgroup with the whole sum over K
+        if (part) return fail(CHIRON_ERR_INVALID_ARG, "linear: the SwiGLU epilogue cannot slice K");
+        if (L.N % 32 != 0) return fail(CHIRON_ERR_SHAPE, "linear: a fused gate/up matrix has a multiple of 32 rows (got %d)", L.N);
+        if (ldy % (epilogue == EPI_SWIGLU ? 4 : 8) != 0 || ((uintptr_t)y & 15))
+            return fail(CHIRON_ERR_INVALID_ARG, "linear: SwiGLU output rows must be 16-byte aligned");
+    }
+    if (asplit && prologue != PRO_PACKED && M >= linear_big_min_rows(L) && tuning().linear_big_all)
+        return launch_linear_big(L, A, lda, M, y, ldy, epilogue, part, max_split, ksplit_out, asplit, st);
     if (L.K % 16 != 0 || L.K < 16) return fail(CHIRON_ERR_SHAPE, "linear: K=%d must be a positive multiple of 16", L.K);
     if (prologue != PRO_PACKED && (lda % 4 != 0 || ((uintptr_t)A & 15)))
         return fail(CHIRON_ERR_INVALID_ARG, "linear: input rows must be 16-byte aligned");
@@ -482,20 +536,17 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
         if (((tiles + 4 * nf - 1) / (4 * nf)) * gz > kNumCU) nf = 2;
     } else {
         nf = M <= 64 ? 1 : 2;
-        const int max_nf = mt == 3 || prologue != PRO_NONE ? 2 : 4;
+        const int max_nf = mt == 3 ? 2 : 4;
         const int chunks64 = (L.K + 63) / 64;
         for (int c = max_nf; c > nf; c /= 2) {
             const int g = ((tiles + 4 * c - 1) / (4 * c)) * gz;
             const int ks = g >= kNumCU ? 1 : (kNumCU / g < max_split ? kNumCU / g : max_split);
-            if (chunks64 / ks >= 12) {
+            if (chunks64 / ks >= 12 && g * ks >= kNumCU * 3 / 4) {  // (and the sliced grid still covers the chip)
                 nf = c;
                 break;
             }
         }
     }
-    // (MT=2, NF=1, KS=4, SwiGLU) is not instantiated: hipcc 7.2 crashes in code generation on that one combination
-    // (the KS=8 build of it compiles but measured slower than two tiles per wave: 45 vs 36 us at 64 rows)
-    if (prologue == PRO_SWIGLU) nf = 2;
     if (prologue == PRO_PACKED) {  // only the large-batch shapes are built for pre-split input
         mt = 4;
         // four column tiles per wave unless K-slicing cannot make up for the smaller grid (one 128-row tile of a
@@ -517,7 +568,7 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     }
     // A projection that cannot slice K (no workspace) runs one workgroup per CU; a ring of 8 k-steps then keeps twice
     // the weight bytes in flight per wave, which measured 9 % faster on the gate/up shape at 64 rows.
-    const bool ks8 = (mt == 2 || (mt == 3 && nf == 1 && prologue == PRO_NONE)) && nf <= 2 && prologue != PRO_PACKED &&
+    const bool ks8 = (mt == 2 || (mt == 3 && nf == 1)) && nf <= 2 && prologue != PRO_PACKED &&
                      (tn.linear_ks == 8 || (tn.linear_ks == 0 && nf == 1 && !part && prologue == PRO_NONE));
     // Up to 32 rows a wave has two MFMAs per k-step and its weight stream is bound by the bytes it keeps in flight over
     // the load latency: the unsliced one-tile-per-wave shape takes a ring of 16 k-steps (16 KiB per wave; measured on the
@@ -544,25 +595,22 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
     if (ksplit < 1) ksplit = 1;
     int cps = (chunks + ksplit - 1) / ksplit;
     ksplit = (chunks + cps - 1) / cps;  // no empty slices
-    int mode = ksplit > 1 ? 2 : (accumulate ? 1 : 0);
+    int mode = ksplit > 1 ? EPI_SLICES : epilogue;
     float* dst = ksplit > 1 ? part : y;
     int ldd = ksplit > 1 ? L.N : ldy;
     size_t part_stride = (size_t)M * L.N;
+    if (epilogue == EPI_SWIGLU_PACKED) {  // ldy: the consumer's padded K
+        ldd = ldy / 8;
+        part_stride = linear_big_split_elems(M, ldy) / 8;
+    }
     int nblocks = (gx * ksplit * gz + 7) / 8 * 8;
-#define CHIRON_LAUNCH(MT_, NF_)                                                                                        \
-    do {                                                                                                                \
-        if (prologue == PRO_SWIGLU)                                                                                     \
-            launch_cfg<MT_, 2, PRO_SWIGLU>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz); \
-        else                                                                                                            \
-            launch_cfg<MT_, NF_, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz); \
-    } while (0)
+#define CHIRON_LAUNCH(MT_, NF_) launch_cfg<MT_, NF_, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz)
     if (ks16) {
         launch_cfg<1, 1, PRO_NONE, 16>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
     } else if (ks8 && mt == 3) {
         launch_cfg<3, 1, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
     } else if (ks8) {
-        if (prologue == PRO_SWIGLU) launch_cfg<2, 2, PRO_SWIGLU, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
-        else if (nf == 1) launch_cfg<2, 1, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
+        if (nf == 1) launch_cfg<2, 1, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else launch_cfg<2, 2, PRO_NONE, 8>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
     } else if (prologue == PRO_PACKED) {
         // several M-tiles re-read the weights through the L2: no streaming hint then
@@ -570,7 +618,7 @@ int32_t launch_linear(const Linear& L, const float* A, int lda, int M, float* y,
         else if (nf == 4) launch_cfg<4, 4, PRO_PACKED>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else if (gz > 1) launch_cfg<4, 2, PRO_PACKED, 4, false>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else launch_cfg<4, 2, PRO_PACKED>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
-    } else if (nf == 4 && prologue != PRO_SWIGLU) {
+    } else if (nf == 4) {
         if (mt == 4 && gz > 1) launch_cfg<4, 4, PRO_NONE, 4, false>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else if (mt == 4) launch_cfg<4, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);
         else launch_cfg<2, 4, PRO_NONE>(nblocks, st, L, A, lda, M, dst, ldd, cps, mode, part_stride, gx, ksplit, gz);

@@ -1,14 +1,14 @@
 // Projections at large row counts (hundreds of requests per step): there the product is bound by the matrix
-// cores, not by the weight stream.  split_pack_kernel turns the fp32 activations (optionally silu(gate)*up) into
-// their two bf16 terms once, stored in the same 32-row x 8-k tile order as the packed weights; the projection
-// kernel then copies those pieces straight from global memory into LDS (no conversion work, no staging
-// registers and no exp() in its loop), which is what lets the SwiGLU projection use the widest tile.
+// cores, not by the weight stream, and the projection kernel is fastest when its activations arrive as their two
+// bf16 terms in the same 32-row x 8-k tile order as the packed weights: it copies those pieces straight from global
+// memory into LDS (no conversion work, no staging registers).  The down projection gets its input in that form from
+// the gate/up projection's epilogue; split_pack_kernel produces it from fp32 rows for any other projection (a knob,
+// off by default: the extra pass costs more than it saves there).
 #include "chiron_internal.h"
 #include "device_util.h"
 
 namespace chiron {
 
-template <int PRO>
 __global__ __launch_bounds__(256) void split_pack_kernel(const float* __restrict__ A, int lda, int M, int K, int Kpad,
                                                          uint16_t* __restrict__ Ah, uint16_t* __restrict__ Al) {
     const int kgroups = Kpad / 8;
@@ -21,12 +21,6 @@ __global__ __launch_bounds__(256) void split_pack_kernel(const float* __restrict
         const float* p = A + (size_t)min(m, M - 1) * lda + min(k, K - 8);
         float4 a0 = *reinterpret_cast<const float4*>(p), a1 = *reinterpret_cast<const float4*>(p + 4);
         float v[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-        if (PRO == PRO_SWIGLU) {
-            float4 u0 = *reinterpret_cast<const float4*>(p + K), u1 = *reinterpret_cast<const float4*>(p + K + 4);
-            float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = v[e] / (1.0f + __expf(-v[e])) * u[e];
-        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = ok ? v[e] : 0.f;
         uint4 hi, lo;
@@ -42,7 +36,7 @@ __global__ __launch_bounds__(256) void split_pack_kernel(const float* __restrict
 
 size_t linear_big_split_elems(int M, int Kpad) { return (size_t)((M + 31) / 32) * 32 * Kpad; }
 
-int32_t launch_linear_big(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int accumulate, int prologue,
+int32_t launch_linear_big(const Linear& L, const float* A, int lda, int M, float* y, int ldy, int epilogue,
                           float* part, int max_split, int* ksplit_out, uint16_t* asplit, hipStream_t st) {
     if (ksplit_out) *ksplit_out = 1;
     if (M == 0) return CHIRON_OK;
@@ -54,11 +48,10 @@ int32_t launch_linear_big(const Linear& L, const float* A, int lda, int M, float
     const int mtiles = (M + 31) / 32, kgroups = L.Kpad / 8;
     {
         dim3 grid((unsigned)((kgroups / 8 < 64) ? (kgroups + 7) / 8 : 64), (unsigned)mtiles);
-        if (prologue == PRO_SWIGLU) launch(split_pack_kernel<PRO_SWIGLU>, dim3(grid), dim3(256), st, A, lda, M, L.K, L.Kpad, ah, al);
-        else launch(split_pack_kernel<PRO_NONE>, dim3(grid), dim3(256), st, A, lda, M, L.K, L.Kpad, ah, al);
+        launch(split_pack_kernel, dim3(grid), dim3(256), st, A, lda, M, L.K, L.Kpad, ah, al);
         CHIRON_HIP(hipGetLastError());
     }
-    return launch_linear(L, reinterpret_cast<const float*>(ah), 0, M, y, ldy, accumulate, PRO_PACKED, part, max_split, ksplit_out,
+    return launch_linear(L, reinterpret_cast<const float*>(ah), 0, M, y, ldy, epilogue, PRO_PACKED, part, max_split, ksplit_out,
                          nullptr, st);
 }
 

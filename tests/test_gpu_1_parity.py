@@ -150,24 +150,57 @@ def test_linear(M, N, K):
     lin.close()
 
 
-@pytest.mark.parametrize("M,N,K", [(4, 256, 688), (64, 512, 1408), (40, 96, 64), (390, 512, 704), (80, 512, 704), (96, 96, 64)])
-def test_swiglu_linear(M, N, K):
-    rng = np.random.default_rng(M + N + K)
-    gu = (rng.standard_normal((M, 2 * K)) * 2).astype(np.float32)
-    W = I.normal((N, K), 0.05, 7, "wd", N, K)
-    print("swiglu_linear", M, N, K, flush=True)
-    lin = B().Linear(W.cuda())
-    got = lin.swiglu(torch.from_numpy(gu).cuda()).cpu().numpy()
-    act = orc.swiglu(gu[:, :K], gu[:, K:])
-    want = orc.linear(act, I.to_numpy_storage(W))
+def ffn_case(M, K, F, N, seed, scale=2.0):
+    """x [M,K] fp32, Wg, Wu [F,K], Wd [N,F] bf16 and the oracle's act = silu(x Wg^T) * (x Wu^T), y = act Wd^T"""
+    rng = np.random.default_rng(seed)
+    x = (rng.standard_normal((M, K)) * scale).astype(np.float32)
+    Wg, Wu = I.normal((F, K), 0.05, 7, "wg", seed), I.normal((F, K), 0.05, 7, "wu", seed)
+    Wd = I.normal((N, F), 0.05, 7, "wd", seed)
+    act = orc.swiglu(orc.linear(x, I.to_numpy_storage(Wg)), orc.linear(x, I.to_numpy_storage(Wu)))
+    return x, Wg, Wu, Wd, act, orc.linear(act, I.to_numpy_storage(Wd))
+
+
+@pytest.mark.parametrize("M,K,F", [(4, 256, 688), (1, 64, 16), (33, 1040, 48), (64, 512, 1408), (40, 64, 96), (96, 256, 2064),
+                                   (130, 512, 704), (390, 256, 1376), (17, 2048, 14336), (300, 256, 14336)])
+def test_gate_up_swiglu(M, K, F):
+    """SwiGLU in the gate/up projection's epilogue: every column of silu(gate) * up against the oracle (a slip in the
+    interleaved packing would pair a gate column with the wrong up column); widths of one 16-column group, of ragged
+    counts of workgroup columns, and the 8B width; rows across the tile shapes."""
+    x, Wg, Wu, _, act, _ = ffn_case(M, K, F, 16, M + K + F)
+    print("gate_up_swiglu", M, K, F, flush=True)
+    gu = B().GateUp(Wg.cuda(), Wu.cuda())
+    got = gu.swiglu(torch.from_numpy(x).cuda()).cpu().numpy()
+    assert np.all(np.isfinite(got))
+    assert rel_err(got, act) <= KERNEL_TOL
+    with pytest.raises(TypeError):
+        gu(torch.from_numpy(x).cuda())
+    gu.close()
+
+
+@pytest.mark.parametrize("M,K,F,N", [(4, 256, 688, 256), (64, 256, 1408, 512), (40, 64, 64, 96), (390, 128, 704, 512), (80, 512, 704, 512),
+                                     (96, 64, 64, 96), (97, 64, 688, 96), (200, 256, 2048, 1024), (513, 128, 688, 512),
+                                     (600, 64, 2048, 256)])
+def test_swiglu_ffn(M, K, F, N):
+    """The feed-forward block as the step runs it: gate/up with the SwiGLU epilogue, then the down projection, the
+    intermediate as fp32 rows (up to 512 rows at these widths) or as tiled bf16 terms (from 513 rows on; F = 688 leaves
+    K padding in the down projection's operand).  test_linear_large_batch_kernel forces the tiled form at other sizes."""
+    x, Wg, Wu, Wd, _, want = ffn_case(M, K, F, N, M + K + F + N)
+    print("swiglu_ffn", M, K, F, N, flush=True)
+    gu, down = B().GateUp(Wg.cuda(), Wu.cuda()), B().Linear(Wd.cuda())
+    xg = torch.from_numpy(x).cuda()
+    got = gu.ffn(down, xg).cpu().numpy()
     assert rel_err(got, want) <= KERNEL_TOL
-    lin.close()
+    y0 = np.random.default_rng(5).standard_normal((M, N)).astype(np.float32)
+    got2 = gu.ffn(down, xg, torch.from_numpy(y0).cuda(), accumulate=True).cpu().numpy()
+    assert rel_err(got2, want + y0) <= KERNEL_TOL
+    gu.close(); down.close()
 
 
 def test_linear_over_seeded_random_shapes():
     """The launch shape (rows per tile, column tiles per wave, K-slices, pre-split input) is chosen from M, N and K by
     several rules: 48 seeded random shapes, widths from a few columns to more than two workgroups per CU and rows
-    across every tile boundary, each against the oracle, plain and with the SwiGLU prologue."""
+    across every tile boundary, each against the oracle; every third shape also as the down projection of a feed-forward
+    block behind a gate/up projection with the SwiGLU epilogue."""
     rng = np.random.default_rng(2024)
     for case in range(48):
         M = int(rng.integers(1, 700))
@@ -181,10 +214,15 @@ def test_linear_over_seeded_random_shapes():
         got = lin(torch.from_numpy(x).cuda()).cpu().numpy()
         assert rel_err(got, want) <= KERNEL_TOL, (M, N, K)
         if case % 3 == 0:
-            gu = (rng.standard_normal((M, 2 * K)) * 2).astype(np.float32)
-            got = lin.swiglu(torch.from_numpy(gu).cuda()).cpu().numpy()
-            want = orc.linear(orc.swiglu(gu[:, :K], gu[:, K:]), I.to_numpy_storage(W))
-            assert rel_err(got, want) <= KERNEL_TOL, (M, N, K, "swiglu")
+            Kin = 16 * int(rng.integers(1, 9))
+            xin = (rng.standard_normal((M, Kin)) * 2).astype(np.float32)
+            Wg, Wu = I.normal((K, Kin), 0.05, 9, "wrg", case), I.normal((K, Kin), 0.05, 9, "wru", case)
+            gu = B().GateUp(Wg.cuda(), Wu.cuda())
+            got = gu.ffn(lin, torch.from_numpy(xin).cuda()).cpu().numpy()
+            act = orc.swiglu(orc.linear(xin, I.to_numpy_storage(Wg)), orc.linear(xin, I.to_numpy_storage(Wu)))
+            want = orc.linear(act, I.to_numpy_storage(W))
+            assert rel_err(got, want) <= KERNEL_TOL, (M, N, K, Kin, "ffn")
+            gu.close()
         lin.close()
 
 
@@ -208,16 +246,13 @@ def test_linear_large_batch_kernel(M, N, K):
         got2 = lin(xg, torch.from_numpy(y0).cuda(), accumulate=True).cpu().numpy()
         assert rel_err(got2, want + y0) <= KERNEL_TOL
         lin.close()
-        if K % 2 == 0:  # SwiGLU input: gate | up halves of width K/2
-            Kh = K // 2
-            Wd = I.normal((N, Kh), 0.05, 9, "wbd", N, Kh)
-            if Kh % 16 == 0:
-                lin = b.Linear(Wd.cuda())
-                gu = (x * 2).astype(np.float32)
-                got3 = lin.swiglu(torch.from_numpy(gu).cuda()).cpu().numpy()
-                want3 = orc.linear(orc.swiglu(gu[:, :Kh], gu[:, Kh:]), I.to_numpy_storage(Wd))
-                assert rel_err(got3, want3) <= KERNEL_TOL
-                lin.close()
+        # the feed-forward block with its intermediate forced into the tiled form at this M: F = K is the width of
+        # the gate/up output and of the down projection's input
+        xs, Wg, Wu, Wd, _, want3 = ffn_case(M, 64, K, N, M + N + K)
+        gu, down = b.GateUp(Wg.cuda(), Wu.cuda()), b.Linear(Wd.cuda())
+        got3 = gu.ffn(down, torch.from_numpy(xs).cuda()).cpu().numpy()
+        assert rel_err(got3, want3) <= KERNEL_TOL
+        gu.close(); down.close()
     finally:
         b.set_tuning("linear_big_min_m", 0)
         b.set_tuning("linear_big_all", 0)
