@@ -70,17 +70,18 @@ def log(*a):
 
 def kernel_algorithmic(m, batch, ctx_tokens):
     """per-launch algorithmic HBM bytes and flops of each kernel class (weights + fp32 activations in/out for the
-    projections; 4*n_kv*d bytes per attended token for attention)"""
+    projections, the gate/up projection writing the F columns of silu(gate)*up at 4 bytes each; 4*n_kv*d bytes per
+    attended token for attention)"""
     H, d, F, V = m["hidden"], m["head_dim"], m["ffn"], m["vocab"]
     qn, kn = m["n_q_heads"] * d, m["n_kv_heads"] * d
     M = batch
 
-    def gemm(N, K, extra_in=0):
-        act = 4 * M * (K + extra_in) + 4 * M * N
+    def gemm(N, K, out_cols=None):
+        act = 4 * M * K + 4 * M * (N if out_cols is None else out_cols)
         return dict(bytes=2 * N * K + act, act_bytes=act, flops=2 * M * N * K)
 
     return {
-        "qkv": gemm(qn + 2 * kn, H), "o": gemm(H, qn), "gateup": gemm(2 * F, H), "down": gemm(H, F, extra_in=F),
+        "qkv": gemm(qn + 2 * kn, H), "o": gemm(H, qn), "gateup": gemm(2 * F, H, out_cols=F), "down": gemm(H, F),
         "lmhead": gemm(V, H),
         "attn": dict(bytes=4 * m["n_kv_heads"] * d * ctx_tokens, flops=4 * m["n_q_heads"] * d * ctx_tokens),
     }
@@ -211,7 +212,7 @@ def main():
         roof = dict(bound="hbm", achieved=round(hbm_frac * HBM_PEAK_GBS, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(hbm_frac, 4), traffic=None)
     roof["kernel"] = {"qkv": "linear_kernel (QKV projection)", "o": "linear_kernel (O projection)",
-                      "gateup": "linear_kernel (gate/up projection)", "down": "linear_kernel (SwiGLU + down projection)",
+                      "gateup": "linear_kernel (gate/up projection + SwiGLU)", "down": "linear_kernel (down projection)",
                       "lmhead": "linear_kernel (LM head)", "attn": "paged_attn_kernel"}[dom]
     roof["avg_us"] = d_us
     roof["algorithmic_bytes_per_launch"] = alg[dom]["bytes"]
