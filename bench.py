@@ -28,11 +28,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # `sha` is the sha256 of the kernel's source file at that time; with any other source the figure is reported null.
 TRAFFIC = {
     # (workload, kernel class): (source file, sha256, fetch bytes, write bytes)
-    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "9ea43d6ce8f3b5dec18572d9db92b9d78c49fc1f9cf2fa199c8deccfc2654ece", 275771900, 4259906),
-    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "86840ff2334c1a164389e1c3887c25aac8c7f3b1eb370b842b0597f8f486e455", 125037157, 16777224),
-    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "86840ff2334c1a164389e1c3887c25aac8c7f3b1eb370b842b0597f8f486e455", 243441252, 7340032),
-    ("llama8b-mixed-sweep512", "attn"): ("attention.hip", "9ea43d6ce8f3b5dec18572d9db92b9d78c49fc1f9cf2fa199c8deccfc2654ece", 4204299961, 37314251),
-    ("llama8b-b32-long32k", "attn"): ("attention.hip", "9ea43d6ce8f3b5dec18572d9db92b9d78c49fc1f9cf2fa199c8deccfc2654ece", 3721964532, 29757940),
+    ("llama8b-b64-lognormal800", "attn"): ("attention.hip", "02217a164f11f306204df37f6e2b724792ba1bdb546d81105e6be8e84d6e4635", 275697032, 4259904),
+    ("llama8b-b64-lognormal800", "gateup"): ("linear.hip", "05a738cc438354e18a9eb186fdc7e1c7d3925e12a706b569264088025053acdc", 243439145, 3670016),
+    ("llama8b-b64-lognormal800", "down"): ("linear.hip", "05a738cc438354e18a9eb186fdc7e1c7d3925e12a706b569264088025053acdc", 121329453, 16777219),
+    ("llama8b-mixed-sweep512", "attn"): ("attention.hip", "02217a164f11f306204df37f6e2b724792ba1bdb546d81105e6be8e84d6e4635", 4197918185, 37881916),
+    ("llama8b-b32-long32k", "attn"): ("attention.hip", "02217a164f11f306204df37f6e2b724792ba1bdb546d81105e6be8e84d6e4635", 3723503215, 30211101),
 }
 
 
