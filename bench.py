@@ -199,6 +199,10 @@ def main():
         if name in alg:
             k["GBps"] = round(alg[name]["bytes"] / (avg_us * 1e-6) / 1e9, 1)
             k["TFLOPs"] = round(alg[name]["flops"] / (avg_us * 1e-6) / 1e12, 2)
+            # the same two figures against the published peaks (algorithmic work: a product issued for both activation
+            # terms counts once)
+            k["frac_of_hbm_peak"] = round(k["GBps"] / HBM_PEAK_GBS, 4)
+            k["frac_of_mfma_peak"] = round(k["TFLOPs"] / MFMA_BF16_PEAK_TFLOPS, 4)
         kernels[name] = k
     step_kernel_ms = sum(ms for ms, n in kt.values()) / max(2, min(a.steps, 10))
     dom = max((n for n in kernels if n in alg), key=lambda n: kt[n][0])
