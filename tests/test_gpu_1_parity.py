@@ -161,7 +161,8 @@ def ffn_case(M, K, F, N, seed, scale=2.0):
 
 
 @pytest.mark.parametrize("M,K,F", [(4, 256, 688), (1, 64, 16), (33, 1040, 48), (64, 512, 1408), (40, 64, 96), (96, 256, 2064),
-                                   (130, 512, 704), (390, 256, 1376), (17, 2048, 14336), (300, 256, 14336)])
+                                   (130, 512, 704), (390, 256, 1376), (17, 2048, 14336), (300, 256, 14336),
+                                   (400, 64, 14336)])  # the 128-row x 4-tile wave shape
 def test_gate_up_swiglu(M, K, F):
     """SwiGLU in the gate/up projection's epilogue: every column of silu(gate) * up against the oracle (a slip in the
     interleaved packing would pair a gate column with the wrong up column); widths of one 16-column group, of ragged
@@ -179,7 +180,7 @@ def test_gate_up_swiglu(M, K, F):
 
 @pytest.mark.parametrize("M,K,F,N", [(4, 256, 688, 256), (64, 256, 1408, 512), (40, 64, 64, 96), (390, 128, 704, 512), (80, 512, 704, 512),
                                      (96, 64, 64, 96), (97, 64, 688, 96), (200, 256, 2048, 1024), (513, 128, 688, 512),
-                                     (600, 64, 2048, 256)])
+                                     (600, 64, 2048, 256), (520, 64, 4096, 64)])  # last: tiled output from the widest wave shape
 def test_swiglu_ffn(M, K, F, N):
     """The feed-forward block as the step runs it: gate/up with the SwiGLU epilogue, then the down projection, the
     intermediate as fp32 rows (up to 512 rows at these widths) or as tiled bf16 terms (from 513 rows on; F = 688 leaves
