@@ -152,7 +152,10 @@ int32_t chiron_kv_swap_in(chiron_kvpool *p, const int32_t *block_table_row, int3
  * modified: the running queue and its lengths belong to the caller's scheduler.
  * Device-resident index arrays are NOT range-checked here (see chiron_validate_step_inputs).
  * batch == 0 is a no-op; batch > max_batch is CHIRON_ERR_BATCH_TOO_LARGE.
- * Calls on one model must not overlap (they share the model's workspace). */
+ * Calls on one model must not overlap (they share the model's workspace).
+ * The call only enqueues kernels on `stream`: no allocation, no memory-set or copy node, no host synchronisation
+ * (outside chiron_kernel_timing_begin/end).  It can therefore be recorded into a HIP graph; a replay reads the index
+ * arrays and writes logits at the addresses recorded, with whatever they hold then. */
 int32_t chiron_decode_step(chiron_model *m, chiron_kvpool *p, const int32_t *block_table, const int32_t *seq_lens,
                            const int32_t *tokens, int32_t batch, float *logits, void *stream);
 

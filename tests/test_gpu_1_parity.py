@@ -531,6 +531,42 @@ def test_repeat_step_is_idempotent_and_profile_runs():
         assert p["lat_ms_median"] > 0 and p["lat_ms_p99"] >= p["lat_ms_median"] and p["tokens_per_s"] > 0
 
 
+def test_decode_step_replays_from_a_hip_graph():
+    """The step only enqueues kernels, so it can be recorded into a HIP graph.  Three replays, each after eager work of
+    the program's own on the same model (a step over another batch size, a host synchronisation) and into a logits
+    buffer overwritten in between, must give the bits of the eager step.  A small attention grid makes the waves draw
+    work items from the ticket counters, which only kernels of the step itself put back to zero."""
+    m = dict(I.LLAMA_8B, name="mid", n_layers=3, hidden=1024, ffn=2816, vocab=4096, n_q_heads=32, n_kv_heads=8)
+    lens = I.lognormal_lengths(70, 300, 1, 1500, np.random.default_rng(8))
+    c = make_case(m=m, seed=8, storage="bf16", seq_lens=lens, poison_unused=True)
+    g = gpu_setup(c, poison=True)
+    b = B()
+    b.set_tuning("attn_grid", 16)
+    try:
+        logits = torch.empty((70, 4096), dtype=torch.float32, device="cuda")
+        step = lambda: b.decode_step(g.model, g.pool, g.block_table, g.seq_lens, g.tokens, logits=logits, batch=70)
+        step()
+        torch.cuda.synchronize()
+        eager = logits.clone()
+        assert torch.isfinite(eager).all()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        torch.cuda.synchronize()
+        for replay in range(3):
+            print("graph replay", replay, flush=True)
+            other = b.decode_step(g.model, g.pool, g.block_table, g.seq_lens, g.tokens, batch=5 + replay)
+            torch.cuda.synchronize()
+            assert (other - eager[:5 + replay]).abs().max() <= 1e-2 * eager.std()  # other tile shapes: not the same bits
+            logits.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(logits, eager), replay
+    finally:
+        b.set_tuning("attn_grid", 0)
+
+
 def test_error_paths_on_device():
     c = make_case(batch=4, seed=7, storage="bf16")
     g = gpu_setup(c)
