@@ -589,3 +589,25 @@ def test_error_paths_on_device():
     with pytest.raises(Bd.ChironError) as e:
         Bd.validate_step_inputs(g.model, g.pool, g.block_table, g.seq_lens, badtok)
     assert e.value.code == -7
+    # the fused gate/up matrix: widths, pairing and use are checked on the host before anything is launched
+    import ctypes as C
+    W = I.normal((48, 64), 0.05, 7, "e_w").cuda()
+    with pytest.raises(Bd.ChironError) as e:
+        Bd.GateUp(W[:40].contiguous(), W[:40].contiguous())  # 40 columns: not a multiple of 16
+    assert e.value.code == -2
+    gu, plain, narrow = Bd.GateUp(W, W), Bd.Linear(I.normal((32, 48), 0.05, 7, "e_d").cuda()), Bd.Linear(I.normal((32, 64), 0.05, 7, "e_n").cuda())
+    x = torch.zeros((3, 64), dtype=torch.float32, device="cuda")
+    y = torch.zeros((3, 96), dtype=torch.float32, device="cuda")
+    lib = Bd.load()
+    ptr = lambda t: C.c_void_p(t.data_ptr())
+    assert lib.chiron_op_linear(gu._h, ptr(x), C.c_int32(3), ptr(y), C.c_int32(0), None) == -1      # no plain product of it
+    assert lib.chiron_op_gate_up_swiglu(plain._h, ptr(x), C.c_int32(3), ptr(y), None) == -1         # not a gate/up matrix
+    with pytest.raises(Bd.ChironError) as e:
+        gu.ffn(narrow, x)                                                                            # 48 columns into 64 inputs
+    assert e.value.code == -2
+    with pytest.raises(Bd.ChironError) as e:
+        gu.ffn(gu, x)                                                                                # a gate/up matrix as the down projection
+    assert e.value.code == -1
+    assert gu.ffn(plain, x).shape == (3, 32) and float(gu.ffn(plain, x).abs().max()) == 0.0        # silu(0) * 0 = 0
+    for l in (gu, plain, narrow):
+        l.close()
