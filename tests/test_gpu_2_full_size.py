@@ -199,6 +199,18 @@ def test_8b_width_two_layers_every_row_of_batch512():
         a = (sub.argmax(1) == want[:b].argmax(1)).mean()
         print("prefix batch %d: max|d|/sigma = %.3e, argmax agreement %.4f" % (b, e, a), flush=True)
         assert e <= STEP_TOL and a >= 0.99
+    # the other form of the feed-forward intermediate (tiled bf16 terms written by the gate/up epilogue, which the step
+    # takes from 513 rows on at this width), forced here so that all 512 rows and a ragged 300 are checked through it
+    B.set_tuning("linear_big_min_m", 97)
+    try:
+        for b in (512, 300):
+            sub = B.decode_step(wl.model, wl.pool, wl.block_table, wl.seq_lens, wl.tokens, batch=b).cpu().numpy()
+            e = np.abs(sub - want[:b]).max() / sig
+            a = (sub.argmax(1) == want[:b].argmax(1)).mean()
+            print("tiled intermediate, batch %d: max|d|/sigma = %.3e, argmax agreement %.4f" % (b, e, a), flush=True)
+            assert e <= STEP_TOL and a >= 0.99
+    finally:
+        B.set_tuning("linear_big_min_m", 0)
     wl.pool.close()
     wl.model.close()
     del wl
